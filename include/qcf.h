@@ -1,0 +1,175 @@
+/*
+ * qcf.h - C ABI of the MI355X (gfx950) per-layer query-centric KV-cache fusion library.
+ *
+ * One decoder layer of the cache-fusion step of QCFuse (Section 3.1, Phases 3-4, and
+ * Section 3.2 of the paper): chunk KV caches that were prefilled independently are
+ * concatenated, the critical layer's keys are scored against the probe rows (user
+ * query + summary anchors), the Top-N context tokens are selected, their Q/K/V are
+ * recomputed, written back, and they attend causally over the patched cache.
+ *
+ *   call order for one layer:
+ *     qcf_rerope -> [critical layer only: qcf_score -> qcf_select] ->
+ *     qcf_recompute_qkv -> qcf_scatter -> qcf_recompute_attn
+ *   (attention runs after the scatter: a recomputed row must see the recomputed K/V
+ *   of the other selected rows, otherwise recomputing every token would not reproduce
+ *   full causal prefill - the paper's "Full Computation" end point.)
+ *
+ * Conventions, for every entry point
+ *   - All tensor pointers are DEVICE pointers (HIP), 16-byte aligned, dense row-major,
+ *     owned by the caller.  Descriptor structs passed by pointer without the `_dev`
+ *     suffix live in HOST memory.  The library never allocates or frees memory; scratch
+ *     comes from a caller-supplied device `workspace` of at least
+ *     qcf_<call>_workspace_bytes(...) bytes (its contents are undefined afterwards).
+ *   - Calls validate their scalar arguments on the host, enqueue kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and return without
+ *     synchronising.  Tables that live on the device (chunk table, offsets, indices)
+ *     cannot be validated on the host: kernels clamp every index they read against the
+ *     totals passed by value, so inconsistent tables give wrong results, never
+ *     out-of-bounds accesses.
+ *   - Empty work (zero rows, zero requests) returns QCF_OK and launches nothing.
+ *   - Supported: dtype f32 or bf16; head_dim 64 or 128; n_q_heads a multiple of
+ *     n_kv_heads; rope_style 0 (pairs (i, i+d/2)) or 1 (pairs (2i, 2i+1)).  Anything
+ *     else returns QCF_ERR_UNSUPPORTED.  On error nothing is enqueued and
+ *     qcf_last_error() describes the problem (thread-local text).
+ *   - Element type of q/k/v/x/w/o buffers is desc->dtype; scores and log-sum-exp are
+ *     float32; offsets are int64; indices and positions are int32.
+ *   - Batches are ragged: request b owns context rows [ctx_off[b], ctx_off[b+1]) of the
+ *     fused cache, probe rows [probe_off[b], probe_off[b+1]) and selected rows
+ *     [sel_off[b], sel_off[b+1]).  Offset arrays have B+1 entries, start at 0, are
+ *     non-decreasing and end at the matching total.
+ */
+#ifndef QCF_H_
+#define QCF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum qcf_status {
+  QCF_OK = 0,
+  QCF_ERR_INVALID_ARG = 1,
+  QCF_ERR_UNSUPPORTED = 2,
+  QCF_ERR_WORKSPACE_TOO_SMALL = 3,
+  QCF_ERR_HIP = 4
+} qcf_status;
+
+enum { QCF_DTYPE_F32 = 0, QCF_DTYPE_BF16 = 1 };
+enum { QCF_ROPE_HALF_SPLIT = 0, QCF_ROPE_INTERLEAVED = 1 };
+
+/* Geometry of one attention layer (host struct). */
+typedef struct qcf_layer_desc {
+  int32_t d_model;     /* hidden size */
+  int32_t n_q_heads;   /* H */
+  int32_t n_kv_heads;  /* H_kv; query head h reads KV head h / (H / H_kv) */
+  int32_t head_dim;    /* d: 64 or 128 */
+  double  rope_base;   /* theta_i = rope_base^(-2i/d) */
+  int32_t rope_style;  /* QCF_ROPE_* */
+  int32_t dtype;       /* QCF_DTYPE_* */
+} qcf_layer_desc;
+
+/* One independently prefilled context chunk (element of a DEVICE array).  The chunk
+ * cache is read-only: it may be shared by many requests at different offsets. */
+typedef struct qcf_chunk {
+  const void* k_src;   /* [len, H_kv, d] keys carrying the rotation of their local positions */
+  const void* v_src;   /* [len, H_kv, d] values (ignored when v_fused is NULL) */
+  int32_t len;         /* tokens in the chunk (> 0) */
+  int32_t src_pos0;    /* local position its first token was prefilled at */
+  int64_t dst_row;     /* first row of the chunk in the fused cache */
+  int32_t dst_pos0;    /* global position of its first token in the fused prompt */
+  int32_t reserved;    /* set to 0 */
+} qcf_chunk;
+
+const char* qcf_status_string(qcf_status s);
+/* Text of the last error raised on the calling thread ("" if none). */
+const char* qcf_last_error(void);
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t qcf_version(void);
+
+/* ---- step 1: re-rotation + concatenation ("location-independent" chunk reuse,
+ * Section 3.2 indexing module / Section 4 scenario 2).
+ * For every chunk c and token t < len: fused K row dst_row + t = key row t with every
+ * rotary pair turned by (dst_pos0 - src_pos0) * theta_i; fused V row = value row t.
+ * chunks_dev: DEVICE array of n_chunks entries sorted by dst_row, ranges disjoint and
+ * inside [0, total_rows); rows covered by no chunk are left untouched.  v_fused may be
+ * NULL (keys only, e.g. loading just the critical layer's K for scoring). */
+size_t qcf_rerope_workspace_bytes(const qcf_layer_desc* desc, int32_t n_chunks, int64_t total_rows);
+qcf_status qcf_rerope(const qcf_layer_desc* desc, const qcf_chunk* chunks_dev, int32_t n_chunks,
+                      int64_t total_rows, void* k_fused, void* v_fused,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- step 2: critical-layer attention analysis (Section 3.1 Phase 3; Section 3.2,
+ * query-related token selector: multi-head attention weights, averaged).
+ * score[j] = mean over the request's probe rows i and all heads h of
+ *            softmax_j( q_probe[i,h] . k_fused[j, h/G] / sqrt(d) ), softmax over the
+ * request's own context rows.  q_probe [total_probe, H, d] holds rotated queries
+ * (anchor rows and user-query rows alike).  probe_limit (NULL = none): per probe row,
+ * the number of leading context rows of its request it may see.  score [total_ctx]
+ * float32; each request's scores sum to 1.  Deterministic: no floating-point atomics. */
+size_t qcf_score_workspace_bytes(const qcf_layer_desc* desc, int32_t B, int64_t total_probe,
+                                 int64_t total_ctx);
+qcf_status qcf_score(const qcf_layer_desc* desc, int32_t B,
+                     const void* q_probe, const int64_t* probe_off_dev, int64_t total_probe,
+                     const void* k_fused, const int64_t* ctx_off_dev, int64_t total_ctx,
+                     const int32_t* probe_limit_dev, float* score,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- step 3: Top-N selection (Section 3.1 Phase 3, "Top-N"; the recompute ratio of
+ * Section 3.2).  Host helper: N = ceil(ratio * T) (guarded by 1e-9), clamped to [0, T]. */
+int64_t qcf_select_count(int64_t T, double ratio);
+/* For request b, the N_b = sel_off[b+1]-sel_off[b] highest-scoring of its context rows,
+ * ties to the lower index, written in ascending order.  Outputs (each may be NULL
+ * except sel_idx): sel_idx = request-local index; sel_row = ctx_off[b] + index (row in
+ * the fused cache / hidden-state matrix); sel_pos = ctx_pos0[b] + index (absolute
+ * position; ctx_pos0_dev NULL = 0).  N_b is clamped to T_b.  Exact and deterministic. */
+size_t qcf_select_workspace_bytes(int32_t B, int64_t total_ctx);
+qcf_status qcf_select(int32_t B, const float* score, const int64_t* ctx_off_dev, int64_t total_ctx,
+                      const int64_t* sel_off_dev, int64_t total_sel, const int32_t* ctx_pos0_dev,
+                      int32_t* sel_idx, int32_t* sel_row, int32_t* sel_pos,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- step 4: Q/K/V of the selected tokens (Section 3.1 Phase 4, discrete token
+ * recomputation).  For m < M: y = x[row(m)] . w_qkv^T, row(m) = x_gather[m] (or m when
+ * x_gather is NULL; indices outside [0, x_rows) produce zero rows), split into H query
+ * heads, H_kv key heads, H_kv value heads; rotary embedding at pos[m] on Q and K.
+ * x [x_rows, d_model]; w_qkv [(H + 2 H_kv) d, d_model]; outputs q_out [M, H, d],
+ * k_out / v_out [M, H_kv, d]; any output pointer may be NULL to skip that part
+ * (e.g. only Q for probe rows).  fp32 accumulation, outputs stored in desc->dtype. */
+size_t qcf_recompute_qkv_workspace_bytes(const qcf_layer_desc* desc, int64_t M);
+qcf_status qcf_recompute_qkv(const qcf_layer_desc* desc, const void* x, int64_t x_rows,
+                             const int32_t* x_gather_dev, int64_t M, const void* w_qkv,
+                             const int32_t* pos_dev, void* q_out, void* k_out, void* v_out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- step 5: write the recomputed K/V rows into the fused cache (Section 3.1 Phase 4,
+ * "updated" KV).  Row dst_rows[m] of k_fused / v_fused <- row m of k_new / v_new; rows
+ * outside [0, total_rows) are skipped; other rows are untouched.  dst_rows must not
+ * repeat.  v_new/v_fused may both be NULL. */
+qcf_status qcf_scatter(const qcf_layer_desc* desc, const void* k_new, const void* v_new,
+                       const int32_t* dst_rows_dev, int64_t M, void* k_fused, void* v_fused,
+                       int64_t total_rows, void* stream);
+
+/* ---- step 6: location-aware sparse causal attention (Section 3.2, the kernel that
+ * takes the table of discrete token indices with their absolute locations).
+ * o[i,h] = sum_j softmax_j( q_sel[i,h] . k_fused[j, h/G] / sqrt(d) ) v_fused[j, h/G]
+ * over the context rows j of row i's request with ctx_pos0[b] + j <= sel_pos[i]
+ * (ctx_pos0_dev NULL = 0).  sel_pos must be non-decreasing inside a request (as
+ * qcf_select produces).  o_out [total_sel, H, d]; lse_out (may be NULL) [total_sel, H]
+ * float32 natural-log sum-exp of the scaled logits.  A row that sees nothing gets a zero
+ * output row and lse = -inf. */
+size_t qcf_recompute_attn_workspace_bytes(const qcf_layer_desc* desc, int32_t B,
+                                          int64_t total_sel, int64_t total_ctx);
+qcf_status qcf_recompute_attn(const qcf_layer_desc* desc, int32_t B,
+                              const void* q_sel, const int32_t* sel_pos_dev,
+                              const int64_t* sel_off_dev, int64_t total_sel,
+                              const void* k_fused, const void* v_fused,
+                              const int64_t* ctx_off_dev, int64_t total_ctx,
+                              const int32_t* ctx_pos0_dev, void* o_out, float* lse_out,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QCF_H_ */

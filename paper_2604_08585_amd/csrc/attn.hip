@@ -1,0 +1,372 @@
+// Step 6: location-aware sparse causal attention (Section 3.2 of the paper): the selected
+// rows, given with their absolute positions, attend over the patched fused cache.
+//
+// bf16 / head_dim 128 path: flash-style online softmax on 32x32x16 MFMA.  A workgroup owns a
+// block of consecutive selected rows times the G query heads of one KV head (128 "rows"), so
+// every K/V tile is loaded once per KV head.  Logits are produced transposed (S^T = K Q^T):
+// a lane then owns one row and the softmax statistics need no cross-lane traffic beyond one
+// exchange between the two lane halves; the probabilities, still in registers, are already
+// the B operand of O^T += V^T P^T.  V tiles are transposed on their way into LDS.  Key tiles
+// wholly above a wave's highest position are skipped, tiles wholly below its lowest run
+// unmasked, only the straddling tiles compare positions.
+//
+// Generic path (f32, or other shapes): one workgroup per (row, head), online softmax over
+// 256-token tiles.
+#include "qcf_internal.h"
+
+namespace qcf {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int find_request(const int64_t* __restrict__ off, int B, int64_t row) {
+  int b = 0;
+  while (b < B && row >= off[b + 1]) ++b;
+  return b;
+}
+
+struct AttnArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  const int32_t* sel_pos;
+  const int64_t* sel_off;
+  const int64_t* ctx_off;
+  const int32_t* ctx_pos0;
+  int64_t total_sel, total_ctx;
+  int B, H, Hkv, G, D;
+  void* o;
+  float* lse;
+  int n_row_blocks;      // upper bound on row blocks over all requests (MFMA path)
+};
+
+// ------------------------------------------------------------------ generic path
+
+template <typename T>
+__global__ __launch_bounds__(256) void attn_generic(AttnArgs a) {
+  __shared__ float sq[128];
+  __shared__ float sp[256];
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t row = blockIdx.x / a.H;
+  const int h = blockIdx.x - (int)row * a.H;
+  const int b = find_request(a.sel_off, a.B, row);
+  if (b >= a.B) return;
+  const int64_t c0 = min(max(a.ctx_off[b], (int64_t)0), a.total_ctx);
+  const int64_t c1 = min(max(a.ctx_off[b + 1], c0), a.total_ctx);
+  const int Tn = (int)(c1 - c0);
+  const int64_t p0 = a.ctx_pos0 ? a.ctx_pos0[b] : 0;
+  const int n_vis = (int)min((int64_t)Tn, max((int64_t)0, (int64_t)a.sel_pos[row] - p0 + 1));
+  const int g = h / a.G, D = a.D;
+  const T* q = static_cast<const T*>(a.q) + (row * a.H + h) * D;
+  const T* kb = static_cast<const T*>(a.k) + (c0 * a.Hkv + g) * D;
+  const T* vb = static_cast<const T*>(a.v) + (c0 * a.Hkv + g) * D;
+  const int64_t kv_stride = (int64_t)a.Hkv * D;
+  if (tid < D) sq[tid] = Elem<T>::load(q + tid) * rsqrtf((float)D);
+  __syncthreads();
+  float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
+  for (int j0 = 0; j0 < n_vis; j0 += 256) {
+    const int j = j0 + tid;
+    float s = -INFINITY;
+    if (j < n_vis) {
+      const T* kr = kb + j * kv_stride;
+      float d = 0.f;
+      for (int c = 0; c < D; ++c) d += sq[c] * Elem<T>::load(kr + c);
+      s = d;
+    }
+    float mx = s;
+    for (int d = 32; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float m_new = fmaxf(m_run, mx);          // finite: the tile has at least one visible token
+    const float p = (j < n_vis) ? expf(s - m_new) : 0.f;
+    sp[tid] = p;
+    float sum = p;
+    for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+    __syncthreads();
+    if (lane == 0) red[wave] = sum;
+    __syncthreads();
+    sum = (red[0] + red[1]) + (red[2] + red[3]);
+    const float alpha = expf(m_run - m_new);       // 0 on the first tile
+    l_run = l_run * alpha + sum;
+    if (tid < D) {
+      acc *= alpha;
+      const int n = min(256, n_vis - j0);
+      for (int jj = 0; jj < n; ++jj) acc += sp[jj] * Elem<T>::load(vb + (j0 + jj) * kv_stride + tid);
+    }
+    m_run = m_new;
+    __syncthreads();
+  }
+  if (tid < D) Elem<T>::store(static_cast<T*>(a.o) + (row * a.H + h) * D + tid, n_vis > 0 ? acc / l_run : 0.f);
+  if (tid == 0 && a.lse) a.lse[row * a.H + h] = n_vis > 0 ? m_run + logf(l_run) : -INFINITY;
+}
+
+// ------------------------------------------------------------------ MFMA path (bf16, d = 128)
+
+constexpr int kBKV = 64;            // tokens per K/V tile
+constexpr int kKStride = 128 + 8;   // bf16 per staged key row
+constexpr int kVStride = kBKV + 8;  // bf16 per staged row of V^T
+constexpr int kKTile = kBKV * kKStride;     // bf16 elements
+constexpr int kVTile = 128 * kVStride;
+constexpr int kStage = kKTile + kVTile;
+constexpr size_t kAttnLds = (size_t)2 * kStage * 2;
+constexpr int kRowsPerWg = 128;     // (selected row, head-in-group) pairs per workgroup
+
+// position of token u (0..63, tile-local) inside a staged V^T row: bits 2 and 3 swapped, so
+// that the eight probabilities a lane holds for one MFMA step are contiguous
+__device__ __forceinline__ int vt_slot(int u) {
+  return (u & ~12) | ((u & 4) << 1) | ((u & 8) >> 1);
+}
+
+__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sbase = reinterpret_cast<bf16_t*>(smem);
+  __shared__ int s_vis_max[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int hf = lane >> 5, l32 = lane & 31;
+  const int g = blockIdx.y;
+  const int BR = kRowsPerWg / a.G;           // selected rows per workgroup
+
+  // locate (request, row block); later blocks (longer key ranges) are scheduled first
+  int wg = a.n_row_blocks - 1 - (int)blockIdx.x;
+  int b = 0;
+  int64_t s0 = 0, s1 = 0;
+  for (; b < a.B; ++b) {
+    s0 = min(max(a.sel_off[b], (int64_t)0), a.total_sel);
+    s1 = min(max(a.sel_off[b + 1], s0), a.total_sel);
+    const int nb = (int)((s1 - s0 + BR - 1) / BR);
+    if (wg < nb) break;
+    wg -= nb;
+  }
+  if (b >= a.B) return;
+  const int64_t c0 = min(max(a.ctx_off[b], (int64_t)0), a.total_ctx);
+  const int64_t c1 = min(max(a.ctx_off[b + 1], c0), a.total_ctx);
+  const int T = (int)(c1 - c0);
+  const int64_t p0 = a.ctx_pos0 ? a.ctx_pos0[b] : 0;
+
+  // this lane's row
+  const int r = wave * 32 + l32;
+  const int64_t srow = s0 + (int64_t)wg * BR + r / a.G;
+  const int head = g * a.G + r % a.G;
+  const bool row_ok = srow < s1;
+  int vis = 0;                                  // number of visible tokens of this row
+  if (row_ok) vis = (int)min((int64_t)T, max((int64_t)0, (int64_t)a.sel_pos[srow] - p0 + 1));
+  int wave_vis_max = vis, wave_vis_min = row_ok ? vis : 0x7fffffff;
+#pragma unroll
+  for (int d = 16; d >= 1; d >>= 1) {
+    wave_vis_max = max(wave_vis_max, __shfl_xor(wave_vis_max, d, 64));
+    wave_vis_min = min(wave_vis_min, __shfl_xor(wave_vis_min, d, 64));
+  }
+  if (lane == 0) s_vis_max[wave] = wave_vis_max;
+  __syncthreads();
+  const int wg_vis_max = max(max(s_vis_max[0], s_vis_max[1]), max(s_vis_max[2], s_vis_max[3]));
+  const int n_tiles = (wg_vis_max + kBKV - 1) / kBKV;
+
+  // stationary query fragments: qf[ks] = row r, elements 16*ks + 8*hf .. +7
+  bf16x8 qf[8];
+  {
+    const bf16_t* qp = static_cast<const bf16_t*>(a.q) + ((row_ok ? srow : 0) * a.H + head) * 128 + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      u32x4 t = u32x4{0u, 0u, 0u, 0u};
+      if (row_ok) t = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+      qf[ks] = __builtin_bit_cast(bf16x8, t);
+    }
+  }
+
+  const bf16_t* kg = static_cast<const bf16_t*>(a.k) + (c0 * a.Hkv + g) * 128;
+  const bf16_t* vg = static_cast<const bf16_t*>(a.v) + (c0 * a.Hkv + g) * 128;
+  const int64_t kv_stride = (int64_t)a.Hkv * 128;
+  // K staging: chunk = tid + 256*i -> token chunk/16, 16-byte part chunk%16
+  // V staging: this thread owns tokens 4*tg .. 4*tg+3 and elements 8*dc .. 8*dc+7
+  const int dc = tid & 15, tg = tid >> 4;
+  u32x4 rk[4], rv[4];
+  auto gload = [&](int t) {
+    const int kv0 = t * kBKV;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int chunk = tid + 256 * i;
+      const int tok = kv0 + (chunk >> 4);
+      rk[i] = u32x4{0u, 0u, 0u, 0u};
+      if (tok < T) rk[i] = *reinterpret_cast<const u32x4*>(kg + tok * kv_stride + (chunk & 15) * 8);
+      const int tokv = kv0 + 4 * tg + i;
+      rv[i] = u32x4{0u, 0u, 0u, 0u};
+      if (tokv < T) rv[i] = *reinterpret_cast<const u32x4*>(vg + tokv * kv_stride + dc * 8);
+    }
+  };
+  auto swrite = [&](int st) {
+    bf16_t* sK = sbase + st * kStage;
+    bf16_t* sV = sK + kKTile;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int chunk = tid + 256 * i;
+      *reinterpret_cast<u32x4*>(sK + (chunk >> 4) * kKStride + (chunk & 15) * 8) = rk[i];
+    }
+    // V^T row R holds element d = 8*(R%16) + R/16; element 8*dc + dd goes to row 16*dd + dc
+    const int slot = vt_slot(4 * tg);
+    const uint32_t w[4][4] = {{rv[0].x, rv[0].y, rv[0].z, rv[0].w}, {rv[1].x, rv[1].y, rv[1].z, rv[1].w},
+                              {rv[2].x, rv[2].y, rv[2].z, rv[2].w}, {rv[3].x, rv[3].y, rv[3].z, rv[3].w}};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {        // dword e of each token holds elements 2e (low) and 2e+1 (high)
+      u32x2 lo, hi;
+      lo.x = (w[0][e] & 0xffffu) | (w[1][e] << 16);
+      lo.y = (w[2][e] & 0xffffu) | (w[3][e] << 16);
+      hi.x = (w[0][e] >> 16) | (w[1][e] & 0xffff0000u);
+      hi.y = (w[2][e] >> 16) | (w[3][e] & 0xffff0000u);
+      *reinterpret_cast<u32x2*>(sV + (16 * (2 * e) + dc) * kVStride + slot) = lo;
+      *reinterpret_cast<u32x2*>(sV + (16 * (2 * e + 1) + dc) * kVStride + slot) = hi;
+    }
+  };
+
+  floatx16 oacc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) oacc[i] = floatx16{0};
+  float m_run = -INFINITY;      // running max of the scaled logits (log2 domain), shared by both lane halves
+  float l_run = 0.f;            // this lane's share of the running denominator
+  const float k2 = kLog2e * 0.08838834764831845f;
+
+  if (n_tiles > 0) {
+    gload(0);
+    swrite(0);
+  }
+  __syncthreads();
+  for (int t = 0; t < n_tiles; ++t) {
+    if (t + 1 < n_tiles) gload(t + 1);
+    const int kv0 = t * kBKV;
+    if (kv0 < wave_vis_max) {
+      const bf16_t* sK = sbase + (t & 1) * kStage;
+      const bf16_t* sV = sK + kKTile;
+      floatx16 s0 = {0}, s1 = {0};
+      const bf16_t* kp = sK + l32 * kKStride + 8 * hf;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + 16 * ks));
+        const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + 32 * kKStride + 16 * ks));
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], s1, 0, 0, 0);
+      }
+      // register v of s0 is token kv0 + 8*(v/4) + 4*hf + v%4 (s1: + 32) against this lane's row
+      float p[32];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { p[v] = s0[v]; p[16 + v] = s1[v]; }
+      if (kv0 + kBKV > wave_vis_min) {
+#pragma unroll
+        for (int v = 0; v < 32; ++v) {
+          const int j = kv0 + 32 * (v >> 4) + 8 * ((v & 15) >> 2) + 4 * hf + (v & 3);
+          if (j >= vis) p[v] = -INFINITY;
+        }
+      }
+      float mx = p[0];
+#pragma unroll
+      for (int v = 1; v < 32; ++v) mx = fmaxf(mx, p[v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx * k2);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = exp2f(m_run - m_use);
+      float sum = 0.f;
+#pragma unroll
+      for (int v = 0; v < 32; ++v) {
+        p[v] = exp2f(p[v] * k2 - m_use);
+        sum += p[v];
+      }
+      l_run = l_run * alpha + sum;
+      m_run = m_new;
+      if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
+      }
+      // P^T fragments: step (mt, t') uses registers 16*mt + 8*t' .. +7
+      bf16x8 pf[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const u32x4 pk = mk4(pack_bf16x2(p[8 * s + 0], p[8 * s + 1]), pack_bf16x2(p[8 * s + 2], p[8 * s + 3]),
+                                    pack_bf16x2(p[8 * s + 4], p[8 * s + 5]), pack_bf16x2(p[8 * s + 6], p[8 * s + 7]));
+        pf[s] = __builtin_bit_cast(bf16x8, pk);
+      }
+      const bf16_t* vp = sV + l32 * kVStride + 8 * hf;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bf16x8 vf = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const u32x4*>(vp + dt * 32 * kVStride + s * 16));
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s], oacc[dt], 0, 0, 0);
+        }
+      }
+    }
+    if (t + 1 < n_tiles) swrite((t + 1) & 1);
+    __syncthreads();
+  }
+
+  // epilogue
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  if (row_ok) {
+    bf16_t* op = static_cast<bf16_t*>(a.o) + (srow * a.H + head) * 128;
+    // staged row R = 32*dt + 8*(v/4) + 4*hf + v%4 is element d = 8*(R%16) + R/16:
+    // for fixed (hb = (v/4)&1, c = v%4) the eight (dt, v/8) values are eight consecutive elements
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = oacc[e >> 1][(e & 1) * 8 + 4 * hb + c] * inv;
+        const int d0 = 64 * hb + 32 * hf + 8 * c;
+        *reinterpret_cast<u32x4*>(op + d0) = Vec16<bf16_t>::pack(f);
+      }
+    }
+    if (a.lse && hf == 0)
+      a.lse[srow * a.H + head] = l_tot > 0.f ? (m_run + log2f(l_tot)) * kLn2 : -INFINITY;
+  }
+}
+
+bool use_mfma(const qcf_layer_desc& L) {
+  const int G = L.n_q_heads / L.n_kv_heads;
+  return L.dtype == QCF_DTYPE_BF16 && L.head_dim == 128 && G <= kRowsPerWg && kRowsPerWg % G == 0;
+}
+
+}  // namespace
+
+size_t attn_workspace(const qcf_layer_desc&, int32_t, int64_t, int64_t) { return 0; }
+
+qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const int32_t* sel_pos,
+                       const int64_t* sel_off, int64_t total_sel, const void* k, const void* v,
+                       const int64_t* ctx_off, int64_t total_ctx, const int32_t* ctx_pos0, void* o,
+                       float* lse, void*, hipStream_t st) {
+  AttnArgs a;
+  a.q = q; a.k = k; a.v = v;
+  a.sel_pos = sel_pos; a.sel_off = sel_off; a.ctx_off = ctx_off; a.ctx_pos0 = ctx_pos0;
+  a.total_sel = total_sel; a.total_ctx = total_ctx;
+  a.B = B; a.H = L.n_q_heads; a.Hkv = L.n_kv_heads; a.G = L.n_q_heads / L.n_kv_heads; a.D = L.head_dim;
+  a.o = o; a.lse = lse;
+  a.n_row_blocks = 0;
+  if (use_mfma(L)) {
+    const int BR = kRowsPerWg / a.G;
+    const int64_t nb = (total_sel + BR - 1) / BR + B;
+    if (nb > 0x7fffffff || a.Hkv > 65535) return fail(QCF_ERR_UNSUPPORTED, "attn: grid too large");
+    a.n_row_blocks = (int)nb;
+    static bool attr_done = false;
+    if (!attr_done) {
+      QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds), "attn attr"));
+      attr_done = true;
+    }
+    attn_mfma_kernel<<<dim3((unsigned)nb, (unsigned)a.Hkv), dim3(256), kAttnLds, st>>>(a);
+    return check_launch("attn");
+  }
+  if (total_sel * a.H > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "attn: grid too large");
+  const dim3 grid((unsigned)(total_sel * a.H)), block(256);
+  if (L.dtype == QCF_DTYPE_BF16) attn_generic<bf16_t><<<grid, block, 0, st>>>(a);
+  else attn_generic<float><<<grid, block, 0, st>>>(a);
+  return check_launch("attn");
+}
+
+}  // namespace qcf

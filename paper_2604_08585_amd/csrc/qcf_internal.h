@@ -1,0 +1,131 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <algorithm>
+#include <cmath>
+
+#include "qcf.h"
+
+namespace qcf {
+
+// ---- host-side error reporting ------------------------------------------------
+qcf_status fail(qcf_status s, const char* fmt, ...);
+qcf_status check_hip(hipError_t e, const char* what);
+qcf_status check_launch(const char* what);
+
+#define QCF_TRY(expr)                 \
+  do {                                \
+    qcf_status _s = (expr);           \
+    if (_s != QCF_OK) return _s;      \
+  } while (0)
+#define QCF_TRY_LAUNCH(what) QCF_TRY(::qcf::check_launch(what))
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int elem_size(int dtype) { return dtype == QCF_DTYPE_BF16 ? 2 : 4; }
+
+// 16-byte and 8-byte register vectors (native vector types, so they live in registers)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 mk4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  u32x4 r = {a, b, c, d};
+  return r;
+}
+
+// ---- storage types --------------------------------------------------------------
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+  return __uint_as_float(static_cast<uint32_t>(v) << 16);
+}
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<bf16_t>(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kVec = 4;   // elements per 16-byte access
+  __device__ static __forceinline__ float load(const float* p) { return *p; }
+  __device__ static __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int kVec = 8;
+  __device__ static __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  __device__ static __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// 16-byte vector <-> float unpacking
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  __device__ static __forceinline__ void unpack(const u32x4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+  __device__ static __forceinline__ u32x4 pack(const float* f) {
+    return mk4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                      __float_as_uint(f[3]));
+  }
+};
+template <> struct Vec16<bf16_t> {
+  __device__ static __forceinline__ void unpack(const u32x4& r, float* f) {
+    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+  __device__ static __forceinline__ u32x4 pack(const float* f) {
+    return mk4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
+                      pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+  }
+};
+
+// ---- launchers (one per translation unit) --------------------------------------
+// Each returns QCF_OK or an error after enqueueing on `st`; arguments were validated
+// by the entry points in api.hip.
+
+size_t rerope_workspace(const qcf_layer_desc& L, int32_t n_chunks, int64_t total_rows);
+qcf_status launch_rerope(const qcf_layer_desc& L, const qcf_chunk* chunks, int32_t n_chunks,
+                         int64_t total_rows, void* kf, void* vf, void* ws, hipStream_t st);
+
+size_t score_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t total_ctx);
+qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const int64_t* probe_off,
+                        int64_t total_probe, const void* k, const int64_t* ctx_off, int64_t total_ctx,
+                        const int32_t* probe_limit, float* score, void* ws, hipStream_t st);
+
+size_t select_workspace(int32_t B, int64_t total_ctx);
+qcf_status launch_select(int32_t B, const float* score, const int64_t* ctx_off, int64_t total_ctx,
+                         const int64_t* sel_off, int64_t total_sel, const int32_t* ctx_pos0,
+                         int32_t* sel_idx, int32_t* sel_row, int32_t* sel_pos, void* ws,
+                         hipStream_t st);
+
+size_t qkv_workspace(const qcf_layer_desc& L, int64_t M);
+qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, const int32_t* gather,
+                      int64_t M, const void* w, const int32_t* pos, void* q, void* k, void* v,
+                      void* ws, hipStream_t st);
+
+qcf_status launch_scatter(const qcf_layer_desc& L, const void* k_new, const void* v_new,
+                          const int32_t* rows, int64_t M, void* kf, void* vf, int64_t total_rows,
+                          hipStream_t st);
+
+size_t attn_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_sel, int64_t total_ctx);
+qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const int32_t* sel_pos,
+                       const int64_t* sel_off, int64_t total_sel, const void* k, const void* v,
+                       const int64_t* ctx_off, int64_t total_ctx, const int32_t* ctx_pos0, void* o,
+                       float* lse, void* ws, hipStream_t st);
+
+// rotary table shared by rerope and qkv: cs[m * (d/2) + i] = (cos, sin)(angle_m * theta_i),
+// angles taken in float64.  `pos` gives one integer per row.
+qcf_status launch_rope_table(const int32_t* pos, int64_t M, int head_dim, double base, float2* cs,
+                             hipStream_t st);
+
+}  // namespace qcf

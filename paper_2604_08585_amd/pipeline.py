@@ -1,0 +1,159 @@
+"""One fused layer = the six library calls in order, on buffers allocated once.
+
+Marshalling only: this module allocates device buffers through torch, builds the small
+offset tables, and enqueues the calls of binding.py on the current stream.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as qb
+from .inputs import Workload, torch_dtype
+
+
+@dataclasses.dataclass
+class DeviceLayer:
+    desc: qb.LayerDesc
+    B: int
+    total_ctx: int
+    total_probe: int
+    total_sel: int
+    n_chunks: int
+    ctx_lens: List[int]
+    sel_counts: List[int]
+    chunk_tensors: list            # keeps the chunk caches alive
+    chunks_dev: torch.Tensor
+    ctx_off: torch.Tensor
+    probe_off: torch.Tensor
+    sel_off: torch.Tensor
+    q_probe: torch.Tensor
+    x_ctx: torch.Tensor
+    w_qkv: torch.Tensor
+    k_fused: torch.Tensor
+    v_fused: torch.Tensor
+    score: torch.Tensor
+    sel_idx: torch.Tensor
+    sel_row: torch.Tensor
+    sel_pos: torch.Tensor
+    q_sel: torch.Tensor
+    k_sel: torch.Tensor
+    v_sel: torch.Tensor
+    o_sel: torch.Tensor
+    lse: torch.Tensor
+    ws_rerope: Optional[torch.Tensor]
+    ws_score: Optional[torch.Tensor]
+    ws_select: Optional[torch.Tensor]
+    ws_qkv: Optional[torch.Tensor]
+    ws_attn: Optional[torch.Tensor]
+
+
+def _ws(nbytes: int, device) -> Optional[torch.Tensor]:
+    return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+
+
+def upload(wl: Workload, device, ratio: Optional[float] = None, shared_chunks: Optional[dict] = None) -> DeviceLayer:
+    """Copy a workload to the device and allocate every buffer the layer needs.
+    `shared_chunks` (uid -> (k, v) tensors) lets several layers or requests share chunk caches."""
+    sh = wl.shape
+    dt = torch_dtype(sh.dtype)
+    desc = qb.make_desc(sh)
+    ratio = wl.ratio if ratio is None else ratio
+    cache = {} if shared_chunks is None else shared_chunks
+
+    def dev_t(a: np.ndarray, dtype=dt) -> torch.Tensor:
+        return torch.from_numpy(np.ascontiguousarray(a)).to(device=device, dtype=dtype)
+
+    chunk_dicts, keep = [], []
+    ctx_off, probe_off, sel_off = [0], [0], [0]
+    row = 0
+    for req in wl.requests:
+        for ch, pos0 in zip(req.chunks, req.dst_pos0):
+            key = ch.uid if ch.uid >= 0 else id(ch)
+            if key not in cache or cache[key][2] is not ch.k:
+                cache[key] = (dev_t(ch.k), dev_t(ch.v), ch.k)
+            kt, vt, _ = cache[key]
+            keep.append((kt, vt))
+            chunk_dicts.append(dict(k=kt, v=vt, src_pos0=ch.src_pos0, dst_row=row, dst_pos0=pos0))
+            row += ch.length
+        ctx_off.append(row)
+        probe_off.append(probe_off[-1] + req.R)
+        sel_off.append(sel_off[-1] + qb.qcf_select_count(req.T, ratio))
+    B = len(wl.requests)
+    total_ctx, total_probe, total_sel = ctx_off[-1], probe_off[-1], sel_off[-1]
+    H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    i64 = lambda v: torch.tensor(v, dtype=torch.int64, device=device)
+    empty = lambda *s, dtype=dt: torch.empty(*s, dtype=dtype, device=device)
+    q_probe = torch.cat([dev_t(r.q_probe) for r in wl.requests]) if total_probe else empty(0, H, D)
+    x_ctx = torch.cat([dev_t(r.x_ctx) for r in wl.requests]) if total_ctx else empty(0, sh.d_model)
+    n_sel = max(total_sel, 1)
+    return DeviceLayer(
+        desc=desc, B=B, total_ctx=total_ctx, total_probe=total_probe, total_sel=total_sel,
+        n_chunks=len(chunk_dicts), ctx_lens=[r.T for r in wl.requests],
+        sel_counts=[sel_off[i + 1] - sel_off[i] for i in range(B)],
+        chunk_tensors=keep, chunks_dev=qb.chunk_table(chunk_dicts, device),
+        ctx_off=i64(ctx_off), probe_off=i64(probe_off), sel_off=i64(sel_off),
+        q_probe=q_probe, x_ctx=x_ctx, w_qkv=dev_t(wl.w_qkv),
+        k_fused=empty(max(total_ctx, 1), Hkv, D), v_fused=empty(max(total_ctx, 1), Hkv, D),
+        score=empty(max(total_ctx, 1), dtype=torch.float32),
+        sel_idx=empty(n_sel, dtype=torch.int32), sel_row=empty(n_sel, dtype=torch.int32),
+        sel_pos=empty(n_sel, dtype=torch.int32),
+        q_sel=empty(n_sel, H, D), k_sel=empty(n_sel, Hkv, D), v_sel=empty(n_sel, Hkv, D),
+        o_sel=empty(n_sel, H, D), lse=empty(n_sel, H, dtype=torch.float32),
+        ws_rerope=_ws(qb.qcf_rerope_workspace_bytes(desc, len(chunk_dicts), total_ctx), device),
+        ws_score=_ws(qb.qcf_score_workspace_bytes(desc, B, total_probe, total_ctx), device),
+        ws_select=_ws(qb.qcf_select_workspace_bytes(B, total_ctx), device),
+        ws_qkv=_ws(qb.qcf_recompute_qkv_workspace_bytes(desc, total_sel), device),
+        ws_attn=_ws(qb.qcf_recompute_attn_workspace_bytes(desc, B, total_sel, total_ctx), device),
+    )
+
+
+def step_rerope(L: DeviceLayer) -> None:
+    qb.qcf_rerope(L.desc, L.chunks_dev, L.n_chunks, L.total_ctx, L.k_fused, L.v_fused, L.ws_rerope)
+
+
+def step_score(L: DeviceLayer) -> None:
+    qb.qcf_score(L.desc, L.B, L.q_probe, L.probe_off, L.total_probe, L.k_fused, L.ctx_off, L.total_ctx,
+                 None, L.score, L.ws_score)
+
+
+def step_select(L: DeviceLayer) -> None:
+    qb.qcf_select(L.B, L.score, L.ctx_off, L.total_ctx, L.sel_off, L.total_sel, None, L.sel_idx, L.sel_row,
+                  L.sel_pos, L.ws_select)
+
+
+def step_qkv(L: DeviceLayer) -> None:
+    qb.qcf_recompute_qkv(L.desc, L.x_ctx, L.total_ctx, L.sel_row, L.total_sel, L.w_qkv, L.sel_pos,
+                         L.q_sel, L.k_sel, L.v_sel, L.ws_qkv)
+
+
+def step_scatter(L: DeviceLayer) -> None:
+    qb.qcf_scatter(L.desc, L.k_sel, L.v_sel, L.sel_row, L.total_sel, L.k_fused, L.v_fused, L.total_ctx)
+
+
+def step_attn(L: DeviceLayer) -> None:
+    qb.qcf_recompute_attn(L.desc, L.B, L.q_sel, L.sel_pos, L.sel_off, L.total_sel, L.k_fused, L.v_fused,
+                          L.ctx_off, L.total_ctx, None, L.o_sel, L.lse, L.ws_attn)
+
+
+STEPS = (("rerope", step_rerope), ("score", step_score), ("select", step_select),
+         ("qkv", step_qkv), ("scatter", step_scatter), ("attn", step_attn))
+
+
+def enqueue_layer(L: DeviceLayer, critical: bool = True) -> None:
+    """rerope -> [score -> select at the critical layer] -> qkv -> scatter -> attn."""
+    for name, fn in STEPS:
+        if not critical and name in ("score", "select"):
+            continue
+        fn(L)
+
+
+def fuse_layer(L: DeviceLayer, critical: bool = True) -> Dict[str, torch.Tensor]:
+    enqueue_layer(L, critical)
+    n = L.total_sel
+    return dict(k_fused=L.k_fused[:L.total_ctx], v_fused=L.v_fused[:L.total_ctx], score=L.score[:L.total_ctx],
+                sel_idx=L.sel_idx[:n], sel_row=L.sel_row[:n], sel_pos=L.sel_pos[:n], q_sel=L.q_sel[:n],
+                k_sel=L.k_sel[:n], v_sel=L.v_sel[:n], o_sel=L.o_sel[:n], lse=L.lse[:n])
