@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-layer KV-cache fusion hot path on one MI355X.
+
+A step is one pass of all six calls (rerope, score, select, recompute_qkv, scatter,
+recompute_attn) over one critical layer of the 8K-context workload (16 ragged chunks, 8192
+context tokens, 80 probe rows, Llama-3-8B-shaped layer, bf16, recompute ratio 15 %).  Inputs
+are resident in HBM before the timed region; several independent copies of the layer's buffers
+are cycled so the working set exceeds the memory-side cache, as the per-layer loop of a real
+model does.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--config", type=int, default=2, help="workload configuration (1..3 fit one GPU)")
+    p.add_argument("--ratio", type=float, default=0.15)
+    p.add_argument("--copies", type=int, default=6, help="independent buffer sets cycled through")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--cpu-sample-rows", type=int, default=256)
+    return p.parse_args()
+
+
+def algorithmic_work(L, sel_pos_host, shape):
+    """Bytes / flops the method itself must move / compute per call (no tile padding, only the
+    unmasked part of the causal attention)."""
+    s = 2 if shape.dtype == "bf16" else 4
+    T, R, N = L.total_ctx, L.total_probe, L.total_sel
+    H, Hkv, D, dm = shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_model
+    kv_row = Hkv * D * s
+    vis = int(sum(int(p) + 1 for p in sel_pos_host))
+    return {
+        "rerope": {"bytes": 4 * T * kv_row, "flops": 0},                              # K and V, read + write
+        "score": {"bytes": T * kv_row + R * H * D * s + 4 * T, "flops": 2 * R * H * T * D},
+        "select": {"bytes": 4 * T + 4 * N, "flops": 0},
+        "qkv": {"bytes": (N * dm + (H + 2 * Hkv) * D * dm + N * (H + 2 * Hkv) * D) * s,
+                "flops": 2 * N * dm * (H + 2 * Hkv) * D},
+        "scatter": {"bytes": 4 * N * kv_row, "flops": 0},
+        "attn": {"bytes": 2 * N * H * D * s + 2 * T * kv_row, "flops": 4 * H * D * vis},
+    }
+
+
+def cpu_baseline(cfg, ratio, sample_rows):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the streaming and
+    scoring steps in full, projection and attention on `sample_rows` selected rows, scaled."""
+    import numpy as np
+    from oracle import qcf_oracle as orc
+    from paper_2604_08585_amd import inputs
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    wl = inputs.make_config(cfg, orc.PlantOps())
+    sh, req = wl.shape, wl.requests[0]
+    t = {}
+    t0 = time.perf_counter()
+    kf, vf = orc.rerope([c.k for c in req.chunks], [c.v for c in req.chunks], req.dst_pos0, sh.rope_base)
+    t["rerope"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    s = orc.score(req.q_probe, kf)
+    t["score"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    n = orc.select_count(req.T, ratio)
+    idx = orc.select(s, n)
+    t["select"] = time.perf_counter() - t0
+    rows = np.sort(np.random.default_rng(0).choice(n, size=min(sample_rows, n), replace=False))
+    scale = n / len(rows)
+    t0 = time.perf_counter()
+    q_s, k_s, v_s = orc.recompute_qkv(req.x_ctx[idx[rows]], wl.w_qkv, idx[rows], sh.n_q_heads, sh.n_kv_heads,
+                                      sh.head_dim, sh.rope_base)
+    t["qkv"] = (time.perf_counter() - t0) * scale
+    t0 = time.perf_counter()
+    kp, vp = orc.scatter(kf, vf, k_s, v_s, idx[rows])
+    t["scatter"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    orc.recompute_attn(q_s, idx[rows], kp, vp)
+    t["attn"] = (time.perf_counter() - t0) * scale
+    total = sum(t.values())
+    return {"value": req.T / total, "unit": "context tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"config {cfg}, ratio {ratio}: rerope/score/select/scatter in full; qkv and attn on "
+                      f"{len(rows)} of {n} selected rows, their time scaled by {scale:.1f}",
+            "ms_per_call": {k: round(v * 1e3, 2) for k, v in t.items()}}
+
+
+def load_traffic(kernel, workload):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
+    the same counters on a copy kernel of known size); kept as text under profiles/."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        table = json.load(open(path))
+        return table.get(workload, {}).get(kernel)
+    except Exception:
+        return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the path is single-GPU by "
+              "design: see DESIGN.md for how it would shard)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2604_08585_amd import binding as qb
+    from paper_2604_08585_amd import inputs, pipeline
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    qb.load_library()          # fails loudly when the HIP library is missing
+
+    wl = inputs.make_config(args.config, pipeline.HipPlantOps(dev))
+    shape, req = wl.shape, wl.requests[0]
+    layers = []
+    for c in range(max(1, args.copies)):
+        layers.append(pipeline.upload(wl, dev, ratio=args.ratio, shared_chunks={}))
+    workload = f"cfg{args.config}: {len(req.chunks)} chunks, T={req.T}, R={req.R}, ratio={args.ratio}, " \
+               f"N={layers[0].total_sel}, d_model={shape.d_model}, H={shape.n_q_heads}/{shape.n_kv_heads}, " \
+               f"d={shape.head_dim}"
+
+    names = [n for n, _ in pipeline.STEPS]
+    for i in range(args.warmup):
+        pipeline.enqueue_layer(layers[i % len(layers)])
+    torch.cuda.synchronize()
+    sel_pos_host = layers[0].sel_pos[:layers[0].total_sel].cpu().numpy()
+
+    # timed region: exactly `steps` layers back to back; events bracket every call on the stream the
+    # kernels are launched on (torch's current stream)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        L = layers[i % len(layers)]
+        ev[i][0].record()
+        for j, (_, fn) in enumerate(pipeline.STEPS):
+            fn(L)
+            ev[i][j + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    per_call = {n: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]))
+                for j, n in enumerate(names)}
+
+    work = algorithmic_work(layers[0], sel_pos_host, shape)
+    kernels = {}
+    for n in names:
+        ms = per_call[n]
+        ent = {"ms": round(ms, 5)}
+        if work[n]["bytes"]:
+            ent["GB/s"] = round(work[n]["bytes"] / (ms * 1e-3) / 1e9, 1)
+        if work[n]["flops"]:
+            ent["TFLOP/s"] = round(work[n]["flops"] / (ms * 1e-3) / 1e12, 2)
+        kernels[n] = ent
+    dominant = max(names, key=lambda n: per_call[n])
+    if dominant in ("qkv", "attn", "score"):
+        achieved = work[dominant]["flops"] / (per_call[dominant] * 1e-3) / 1e12
+        roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(achieved, 2),
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4)}
+    else:
+        achieved = work[dominant]["bytes"] / (per_call[dominant] * 1e-3) / 1e9
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4)}
+    roofline["traffic"] = load_traffic(dominant, f"cfg{args.config}_r{args.ratio}")
+    roofline["avg_launch_ms"] = round(per_call[dominant], 5)
+
+    out = {
+        "metric": "fused-layer context tokens/sec + per-layer fusion latency (ms) at 8K ctx",
+        "value": round(req.T / (ms_per_step * 1e-3), 1),
+        "unit": "context tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": workload, "buffer_copies": len(layers)},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, args.ratio, args.cpu_sample_rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -157,3 +157,39 @@ def fuse_layer(L: DeviceLayer, critical: bool = True) -> Dict[str, torch.Tensor]
     return dict(k_fused=L.k_fused[:L.total_ctx], v_fused=L.v_fused[:L.total_ctx], score=L.score[:L.total_ctx],
                 sel_idx=L.sel_idx[:n], sel_row=L.sel_row[:n], sel_pos=L.sel_pos[:n], q_sel=L.q_sel[:n],
                 k_sel=L.k_sel[:n], v_sel=L.v_sel[:n], o_sel=L.o_sel[:n], lse=L.lse[:n])
+
+
+class HipPlantOps:
+    """Backend for inputs.assemble() that borrows the two method operations of the planting
+    recipe from the GPU library (used where the CPU oracle must not be: the benchmark)."""
+
+    def __init__(self, device):
+        self.device = device
+
+    def project_qkv(self, shape, x, w_qkv, pos):
+        dt = torch_dtype(shape.dtype)
+        desc = qb.make_desc(shape)
+        M = int(x.shape[0])
+        xd = torch.from_numpy(np.ascontiguousarray(x)).to(device=self.device, dtype=dt)
+        wd = torch.from_numpy(np.ascontiguousarray(w_qkv)).to(device=self.device, dtype=dt)
+        pd = torch.from_numpy(np.asarray(pos, dtype=np.int32)).to(self.device)
+        q = torch.empty(M, shape.n_q_heads, shape.head_dim, dtype=dt, device=self.device)
+        k = torch.empty(M, shape.n_kv_heads, shape.head_dim, dtype=dt, device=self.device)
+        v = torch.empty(M, shape.n_kv_heads, shape.head_dim, dtype=dt, device=self.device)
+        qb.qcf_recompute_qkv(desc, xd, M, None, M, wd, pd, q, k, v)
+        torch.cuda.synchronize()
+        f = lambda t: t.float().cpu().numpy()
+        return f(q), f(k), f(v)
+
+    def shift_keys(self, shape, k_rows, delta):
+        dt = torch_dtype(shape.dtype)
+        desc = qb.make_desc(shape)
+        n = int(k_rows.shape[0])
+        # the planted target is not yet rounded to the storage dtype: shift it in fp32
+        desc32 = qb.make_desc(dataclasses.replace(shape, dtype="f32"))
+        kd = torch.from_numpy(np.ascontiguousarray(k_rows, dtype=np.float32)).to(self.device)
+        table = qb.chunk_table([dict(k=kd, v=None, src_pos0=0, dst_row=0, dst_pos0=int(delta))], self.device)
+        out = torch.empty_like(kd)
+        qb.qcf_rerope(desc32, table, 1, n, out, None)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
