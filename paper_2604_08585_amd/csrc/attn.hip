@@ -108,32 +108,44 @@ __global__ __launch_bounds__(256) void attn_generic(AttnArgs a) {
 
 // ------------------------------------------------------------------ MFMA path (bf16, d = 128)
 
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
 constexpr int kBKV = 64;            // tokens per K/V tile
-constexpr int kKStride = 128 + 8;   // bf16 per staged key row
-constexpr int kVStride = kBKV + 8;  // bf16 per staged row of V^T
+constexpr int kKStride = 128 + 8;   // bf16 per staged key row: 272 B, conflict-free 16-byte row reads
+constexpr int kVStride = 128 + 32;  // bf16 per staged value row: 320 B, conflict-free transposing reads
 constexpr int kKTile = kBKV * kKStride;     // bf16 elements
-constexpr int kVTile = 128 * kVStride;
+constexpr int kVTile = kBKV * kVStride;
 constexpr int kStage = kKTile + kVTile;
 constexpr size_t kAttnLds = (size_t)2 * kStage * 2;
 constexpr int kRowsPerWg = 128;     // (selected row, head-in-group) pairs per workgroup
 
-// position of token u (0..63, tile-local) inside a staged V^T row: bits 2 and 3 swapped, so
-// that the eight probabilities a lane holds for one MFMA step are contiguous
-__device__ __forceinline__ int vt_slot(int u) {
-  return (u & ~12) | ((u & 4) << 1) | ((u & 8) >> 1);
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  const floatx2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
-__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
+// LDS transposing read: within each group of 16 lanes, lane i receives element i%4 of the four
+// 8-byte rows addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4 of the group.
+__device__ __forceinline__ shortx4 lds_read_tr(const bf16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (shortx4 __attribute__((address_space(3)))*)(const_cast<bf16_t*>(p)));
+}
+
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t* sbase = reinterpret_cast<bf16_t*>(smem);
   __shared__ int s_vis_max[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int hf = lane >> 5, l32 = lane & 31;
-  const int g = blockIdx.y;
   const int BR = kRowsPerWg / a.G;           // selected rows per workgroup
 
-  // locate (request, row block); later blocks (longer key ranges) are scheduled first
-  int wg = a.n_row_blocks - 1 - (int)blockIdx.x;
+  // consecutive workgroup ids land on different XCDs: give each XCD its own KV heads so that a
+  // head's keys and values stay in one L2; later row blocks (longer key ranges) are scheduled first
+  const int g = (int)(blockIdx.x % a.Hkv);
+  int wg = a.n_row_blocks - 1 - (int)(blockIdx.x / a.Hkv);
   int b = 0;
   int64_t s0 = 0, s1 = 0;
   for (; b < a.B; ++b) {
@@ -166,15 +178,24 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
   __syncthreads();
   const int wg_vis_max = max(max(s_vis_max[0], s_vis_max[1]), max(s_vis_max[2], s_vis_max[3]));
   const int n_tiles = (wg_vis_max + kBKV - 1) / kBKV;
+  if (n_tiles == 0) {                 // nothing visible to any row of the block
+    if (row_ok) {
+      bf16_t* op = static_cast<bf16_t*>(a.o) + (srow * a.H + head) * 128 + 64 * hf;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(op + 8 * i) = u32x4{0u, 0u, 0u, 0u};
+      if (a.lse && hf == 0) a.lse[srow * a.H + head] = -INFINITY;
+    }
+    return;
+  }
 
   // stationary query fragments: qf[ks] = row r, elements 16*ks + 8*hf .. +7
   bf16x8 qf[8];
   {
-    const bf16_t* qp = static_cast<const bf16_t*>(a.q) + ((row_ok ? srow : 0) * a.H + head) * 128 + 8 * hf;
+    const bf16_t* qp = static_cast<const bf16_t*>(a.q) + ((row_ok ? srow : s0) * a.H + head) * 128 + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      u32x4 t = u32x4{0u, 0u, 0u, 0u};
-      if (row_ok) t = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+      u32x4 t = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+      if (!row_ok) t = u32x4{0u, 0u, 0u, 0u};
       qf[ks] = __builtin_bit_cast(bf16x8, t);
     }
   }
@@ -182,21 +203,16 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
   const bf16_t* kg = static_cast<const bf16_t*>(a.k) + (c0 * a.Hkv + g) * 128;
   const bf16_t* vg = static_cast<const bf16_t*>(a.v) + (c0 * a.Hkv + g) * 128;
   const int64_t kv_stride = (int64_t)a.Hkv * 128;
-  // K staging: chunk = tid + 256*i -> token chunk/16, 16-byte part chunk%16
-  // V staging: this thread owns tokens 4*tg .. 4*tg+3 and elements 8*dc .. 8*dc+7
-  const int dc = tid & 15, tg = tid >> 4;
+  // staging: chunk = tid + 256*i -> token chunk/16 of the tile, 16-byte part chunk%16; tokens past
+  // the end of the context are clamped (their probabilities are zero)
+  const int st_tok = tid >> 4, st_part = (tid & 15) * 8;
   u32x4 rk[4], rv[4];
   auto gload = [&](int t) {
-    const int kv0 = t * kBKV;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int chunk = tid + 256 * i;
-      const int tok = kv0 + (chunk >> 4);
-      rk[i] = u32x4{0u, 0u, 0u, 0u};
-      if (tok < T) rk[i] = *reinterpret_cast<const u32x4*>(kg + tok * kv_stride + (chunk & 15) * 8);
-      const int tokv = kv0 + 4 * tg + i;
-      rv[i] = u32x4{0u, 0u, 0u, 0u};
-      if (tokv < T) rv[i] = *reinterpret_cast<const u32x4*>(vg + tokv * kv_stride + dc * 8);
+      const int tok = min(t * kBKV + st_tok + 16 * i, T - 1);
+      rk[i] = *reinterpret_cast<const u32x4*>(kg + tok * kv_stride + st_part);
+      rv[i] = *reinterpret_cast<const u32x4*>(vg + tok * kv_stride + st_part);
     }
   };
   auto swrite = [&](int st) {
@@ -204,22 +220,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
     bf16_t* sV = sK + kKTile;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int chunk = tid + 256 * i;
-      *reinterpret_cast<u32x4*>(sK + (chunk >> 4) * kKStride + (chunk & 15) * 8) = rk[i];
-    }
-    // V^T row R holds element d = 8*(R%16) + R/16; element 8*dc + dd goes to row 16*dd + dc
-    const int slot = vt_slot(4 * tg);
-    const uint32_t w[4][4] = {{rv[0].x, rv[0].y, rv[0].z, rv[0].w}, {rv[1].x, rv[1].y, rv[1].z, rv[1].w},
-                              {rv[2].x, rv[2].y, rv[2].z, rv[2].w}, {rv[3].x, rv[3].y, rv[3].z, rv[3].w}};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {        // dword e of each token holds elements 2e (low) and 2e+1 (high)
-      u32x2 lo, hi;
-      lo.x = (w[0][e] & 0xffffu) | (w[1][e] << 16);
-      lo.y = (w[2][e] & 0xffffu) | (w[3][e] << 16);
-      hi.x = (w[0][e] >> 16) | (w[1][e] & 0xffff0000u);
-      hi.y = (w[2][e] >> 16) | (w[3][e] & 0xffff0000u);
-      *reinterpret_cast<u32x2*>(sV + (16 * (2 * e) + dc) * kVStride + slot) = lo;
-      *reinterpret_cast<u32x2*>(sV + (16 * (2 * e + 1) + dc) * kVStride + slot) = hi;
+      *reinterpret_cast<u32x4*>(sK + (st_tok + 16 * i) * kKStride + st_part) = rk[i];
+      *reinterpret_cast<u32x4*>(sV + (st_tok + 16 * i) * kVStride + st_part) = rv[i];
     }
   };
 
@@ -230,10 +232,17 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
   float l_run = 0.f;            // this lane's share of the running denominator
   const float k2 = kLog2e * 0.08838834764831845f;
 
-  if (n_tiles > 0) {
-    gload(0);
-    swrite(0);
-  }
+  // per-lane offsets of the fragment reads
+  const int k_off = l32 * kKStride + 8 * hf;
+  // values: the lane addresses the 8-byte piece (token 4*hf + (lane%16)/4, elements d0 .. d0+3) where
+  // block q = 4*((lane/16)%2) + lane%4 of the 32-element slice starts at d0 = 16*(q%2) + 4*(q/2); after the
+  // transposing read lane (row i = lane%32) then holds four consecutive tokens of element
+  // 16*(i/4 % 2) + 4*(i/8) + i%4, which makes MFMA output row 8b + 4h + c element 16h + 4b + c
+  const int vq = 4 * ((lane >> 4) & 1) + (lane & 3);
+  const int v_off = (4 * hf + ((lane & 15) >> 2)) * kVStride + 16 * (vq & 1) + 4 * (vq >> 1);
+
+  gload(0);
+  swrite(0);
   __syncthreads();
   for (int t = 0; t < n_tiles; ++t) {
     if (t + 1 < n_tiles) gload(t + 1);
@@ -241,24 +250,24 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
     if (kv0 < wave_vis_max) {
       const bf16_t* sK = sbase + (t & 1) * kStage;
       const bf16_t* sV = sK + kKTile;
-      floatx16 s0 = {0}, s1 = {0};
-      const bf16_t* kp = sK + l32 * kKStride + 8 * hf;
+      floatx16 sa = {0}, sb = {0};
+      const bf16_t* kp = sK + k_off;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + 16 * ks));
         const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + 32 * kKStride + 16 * ks));
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], s1, 0, 0, 0);
+        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], sb, 0, 0, 0);
       }
-      // register v of s0 is token kv0 + 8*(v/4) + 4*hf + v%4 (s1: + 32) against this lane's row
+      // register v of sa is token kv0 + 8*(v/4) + 4*hf + v%4 (sb: + 32) against this lane's row
       float p[32];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { p[v] = s0[v]; p[16 + v] = s1[v]; }
+      for (int v = 0; v < 16; ++v) { p[v] = sa[v]; p[16 + v] = sb[v]; }
       if (kv0 + kBKV > wave_vis_min) {
 #pragma unroll
         for (int v = 0; v < 32; ++v) {
           const int j = kv0 + 32 * (v >> 4) + 8 * ((v & 15) >> 2) + 4 * hf + (v & 3);
-          if (j >= vis) p[v] = -INFINITY;
+          p[v] = (j < vis) ? p[v] : -INFINITY;
         }
       }
       float mx = p[0];
@@ -267,11 +276,11 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m_run, mx * k2);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = exp2f(m_run - m_use);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
       float sum = 0.f;
 #pragma unroll
       for (int v = 0; v < 32; ++v) {
-        p[v] = exp2f(p[v] * k2 - m_use);
+        p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(p[v], k2, -m_use));
         sum += p[v];
       }
       l_run = l_run * alpha + sum;
@@ -282,22 +291,23 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
       }
-      // P^T fragments: step (mt, t') uses registers 16*mt + 8*t' .. +7
+      // P^T fragments: step s = 2*mt + t' uses registers 8*s .. 8*s+7 (tokens 16*s + 8*(e/4) + 4*hf + e%4)
       bf16x8 pf[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const u32x4 pk = mk4(pack_bf16x2(p[8 * s + 0], p[8 * s + 1]), pack_bf16x2(p[8 * s + 2], p[8 * s + 3]),
-                                    pack_bf16x2(p[8 * s + 4], p[8 * s + 5]), pack_bf16x2(p[8 * s + 6], p[8 * s + 7]));
+        const u32x4 pk = mk4(cvt_pk_bf16(p[8 * s + 0], p[8 * s + 1]), cvt_pk_bf16(p[8 * s + 2], p[8 * s + 3]),
+                             cvt_pk_bf16(p[8 * s + 4], p[8 * s + 5]), cvt_pk_bf16(p[8 * s + 6], p[8 * s + 7]));
         pf[s] = __builtin_bit_cast(bf16x8, pk);
       }
-      const bf16_t* vp = sV + l32 * kVStride + 8 * hf;
+      const bf16_t* vp = sV + v_off;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 vf = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const u32x4*>(vp + dt * 32 * kVStride + s * 16));
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s], oacc[dt], 0, 0, 0);
+          const shortx4 lo = lds_read_tr(vp + (16 * s) * kVStride + 32 * dt);
+          const shortx4 hi = lds_read_tr(vp + (16 * s + 8) * kVStride + 32 * dt);
+          const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[s], oacc[dt], 0, 0, 0);
         }
       }
     }
@@ -305,22 +315,20 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
     __syncthreads();
   }
 
-  // epilogue
+  // epilogue: output register v of tile dt is element 32*dt + 16*hf + v of this lane's row
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (row_ok) {
-    bf16_t* op = static_cast<bf16_t*>(a.o) + (srow * a.H + head) * 128;
-    // staged row R = 32*dt + 8*(v/4) + 4*hf + v%4 is element d = 8*(R%16) + R/16:
-    // for fixed (hb = (v/4)&1, c = v%4) the eight (dt, v/8) values are eight consecutive elements
+    bf16_t* op = static_cast<bf16_t*>(a.o) + (srow * a.H + head) * 128 + 16 * hf;
 #pragma unroll
-    for (int hb = 0; hb < 2; ++hb) {
+    for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        float f[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = oacc[e >> 1][(e & 1) * 8 + 4 * hb + c] * inv;
-        const int d0 = 64 * hb + 32 * hf + 8 * c;
-        *reinterpret_cast<u32x4*>(op + d0) = Vec16<bf16_t>::pack(f);
+      for (int h8 = 0; h8 < 2; ++h8) {
+        const u32x4 pk = mk4(cvt_pk_bf16(oacc[dt][8 * h8 + 0] * inv, oacc[dt][8 * h8 + 1] * inv),
+                             cvt_pk_bf16(oacc[dt][8 * h8 + 2] * inv, oacc[dt][8 * h8 + 3] * inv),
+                             cvt_pk_bf16(oacc[dt][8 * h8 + 4] * inv, oacc[dt][8 * h8 + 5] * inv),
+                             cvt_pk_bf16(oacc[dt][8 * h8 + 6] * inv, oacc[dt][8 * h8 + 7] * inv));
+        *reinterpret_cast<u32x4*>(op + 32 * dt + 8 * h8) = pk;
       }
     }
     if (a.lse && hf == 0)
@@ -351,7 +359,7 @@ qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const 
   if (use_mfma(L)) {
     const int BR = kRowsPerWg / a.G;
     const int64_t nb = (total_sel + BR - 1) / BR + B;
-    if (nb > 0x7fffffff || a.Hkv > 65535) return fail(QCF_ERR_UNSUPPORTED, "attn: grid too large");
+    if (nb * a.Hkv > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "attn: grid too large");
     a.n_row_blocks = (int)nb;
     static bool attr_done = false;
     if (!attr_done) {
@@ -359,7 +367,7 @@ qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const 
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds), "attn attr"));
       attr_done = true;
     }
-    attn_mfma_kernel<<<dim3((unsigned)nb, (unsigned)a.Hkv), dim3(256), kAttnLds, st>>>(a);
+    attn_mfma_kernel<<<dim3((unsigned)(nb * a.Hkv)), dim3(256), kAttnLds, st>>>(a);
     return check_launch("attn");
   }
   if (total_sel * a.H > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "attn: grid too large");
