@@ -12,6 +12,8 @@
 //
 // Generic path (f32, or other shapes): one workgroup per (row, head), online softmax over
 // 256-token tiles.
+#include <type_traits>
+
 #include "qcf_internal.h"
 
 namespace qcf {
@@ -113,14 +115,12 @@ typedef short shortx8 __attribute__((ext_vector_type(8)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kBKV = 64;            // tokens per K/V tile
-constexpr int kKStride = 128 + 8;   // bf16 per staged key row: 272 B, conflict-free 16-byte row reads
-constexpr int kVStride = 128 + 32;  // bf16 per staged value row: 320 B, conflict-free transposing reads
-constexpr int kKTile = kBKV * kKStride;     // bf16 elements
-constexpr int kVTile = kBKV * kVStride;
+constexpr int kBKV = 64;                    // tokens per K/V tile
+constexpr int kKTile = kBKV * 128;          // bf16 elements; rows are 256 B, no padding (swizzled instead)
+constexpr int kVTile = kBKV * 128;
 constexpr int kStage = kKTile + kVTile;
 constexpr size_t kAttnLds = (size_t)2 * kStage * 2;
-constexpr int kRowsPerWg = 128;     // (selected row, head-in-group) pairs per workgroup
+constexpr int kRowsPerWg = 128;             // (selected row, head-in-group) pairs per workgroup
 
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   const floatx2 f = {lo, hi};
@@ -129,11 +129,33 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
 
 // LDS transposing read: within each group of 16 lanes, lane i receives element i%4 of the four
 // 8-byte rows addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4 of the group.
-__device__ __forceinline__ shortx4 lds_read_tr(const bf16_t* p) {
+__device__ __forceinline__ shortx4 lds_read_tr(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (shortx4 __attribute__((address_space(3)))*)(const_cast<bf16_t*>(p)));
+      (shortx4 __attribute__((address_space(3)))*)(const_cast<unsigned char*>(p)));
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane L lands at lds + 16*L.  Issued through
+// inline assembly so that the compiler does not count it among the loads it waits for before LDS
+// reads: the kernel waits for these loads itself, once per tile, just before the barrier.
+__device__ __forceinline__ void load_to_lds(const void* base, uint32_t lane_off, bf16_t* lds) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(lds));
+  const uint64_t b = (uint64_t)(uintptr_t)base;     // wave-uniform: goes to a scalar register pair
+  // the builtin returns a signed int: widen through uint32_t, or a low half >= 2^31 would smear ones
+  // over the high half of the address
+  const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
+                      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_off), "s"(sb), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+// Tile layouts in LDS (rows of 256 bytes = 16 chunks of 16 bytes, no padding):
+//   keys:   chunk c of token row r sits in slot c ^ (r % 16), so the 16-byte reads of 16 consecutive
+//           rows at one chunk index touch 16 different bank groups;
+//   values: chunk c of row r sits in slot c ^ (4 * (r % 4)), so the 8-byte transposing reads of
+//           8 consecutive rows x 64 bytes touch every bank exactly twice.
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t* sbase = reinterpret_cast<bf16_t*>(smem);
@@ -188,6 +210,37 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     return;
   }
 
+  // asynchronous tile loads: instruction i of wave w fills rows 16*i + 4*w .. +3 (1 KB); lane L
+  // fills slot L%16 of row 16*i + 4*w + L/16 with the chunk the swizzle assigns to that slot.
+  // Tokens past the end of the context are clamped (their probabilities are zero).
+  const bf16_t* kg = static_cast<const bf16_t*>(a.k) + (c0 * a.Hkv + g) * 128;
+  const bf16_t* vg = static_cast<const bf16_t*>(a.v) + (c0 * a.Hkv + g) * 128;
+  const int64_t kv_stride = (int64_t)a.Hkv * 128;
+  const int ld_row = 4 * wave + (lane >> 4);                      // + 16*i
+  const uint32_t row_bytes = (uint32_t)a.Hkv * 256u;              // one token row of the cache
+  const uint32_t ld_kchunk = (uint32_t)(((lane & 15) ^ ld_row) * 16);           // row % 16 == ld_row
+  const uint32_t ld_vchunk = (uint32_t)(((lane & 15) ^ (4 * (ld_row & 3))) * 16);
+  const uint32_t ld_koff = (uint32_t)ld_row * row_bytes + ld_kchunk;
+  const uint32_t ld_voff = (uint32_t)ld_row * row_bytes + ld_vchunk;
+  auto aload = [&](const bf16_t* src, uint32_t off0, uint32_t chunk, int t, bf16_t* dst) {
+    const char* base = reinterpret_cast<const char*>(src) + (int64_t)t * kBKV * row_bytes;
+    if (t * kBKV + kBKV <= T) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) load_to_lds(base + (size_t)(16 * i) * row_bytes, off0, dst + (16 * i) * 128);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = min(16 * i + ld_row, T - 1 - t * kBKV);
+        load_to_lds(base, (uint32_t)row * row_bytes + chunk, dst + (16 * i) * 128);
+      }
+    }
+  };
+  auto aload_k = [&](int t, int st) { aload(kg, ld_koff, ld_kchunk, t, sbase + st * kStage + (4 * wave) * 128); };
+  auto aload_v = [&](int t, int st) {
+    aload(vg, ld_voff, ld_vchunk, t, sbase + st * kStage + kKTile + (4 * wave) * 128);
+  };
+  aload_k(0, 0);
+
   // stationary query fragments: qf[ks] = row r, elements 16*ks + 8*hf .. +7
   bf16x8 qf[8];
   {
@@ -200,30 +253,23 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     }
   }
 
-  const bf16_t* kg = static_cast<const bf16_t*>(a.k) + (c0 * a.Hkv + g) * 128;
-  const bf16_t* vg = static_cast<const bf16_t*>(a.v) + (c0 * a.Hkv + g) * 128;
-  const int64_t kv_stride = (int64_t)a.Hkv * 128;
-  // staging: chunk = tid + 256*i -> token chunk/16 of the tile, 16-byte part chunk%16; tokens past
-  // the end of the context are clamped (their probabilities are zero)
-  const int st_tok = tid >> 4, st_part = (tid & 15) * 8;
-  u32x4 rk[4], rv[4];
-  auto gload = [&](int t) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int tok = min(t * kBKV + st_tok + 16 * i, T - 1);
-      rk[i] = *reinterpret_cast<const u32x4*>(kg + tok * kv_stride + st_part);
-      rv[i] = *reinterpret_cast<const u32x4*>(vg + tok * kv_stride + st_part);
-    }
-  };
-  auto swrite = [&](int st) {
-    bf16_t* sK = sbase + st * kStage;
-    bf16_t* sV = sK + kKTile;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<u32x4*>(sK + (st_tok + 16 * i) * kKStride + st_part) = rk[i];
-      *reinterpret_cast<u32x4*>(sV + (st_tok + 16 * i) * kVStride + st_part) = rv[i];
-    }
-  };
+  // Per-lane byte addresses of the fragment reads inside a stage.
+  //  keys: token row l32, chunk 2*ks + hf lives in slot (2*ks + hf) ^ (l32 % 16); since 2*ks and hf
+  //  occupy different bits, the address of step ks is kb0 ^ (32 * ks).
+  const int kb0 = l32 * 256 + ((hf ^ (l32 & 15)) * 16);
+  //  values: the lane addresses the 8-byte piece (token 4*hf + (lane%16)/4, elements d0 .. d0+3) where
+  //  block q = 4*((lane/16)%2) + lane%4 of a 32-element slice starts at d0 = 16*(q%2) + 4*(q/2); after the
+  //  transposing read lane (row i = lane%32) holds four consecutive tokens of element
+  //  16*(i/4 % 2) + 4*(i/8) + i%4, which makes MFMA output row 8b + 4h + c element 16h + 4b + c.
+  //  Chunk 4*dt + d0/8 of row r lives in slot (4*dt + d0/8) ^ (4 * (r % 4)): the address of output tile
+  //  dt is vb0 ^ (64 * dt).
+  int vb0;
+  {
+    const int vq = 4 * ((lane >> 4) & 1) + (lane & 3);
+    const int d0 = 16 * (vq & 1) + 4 * (vq >> 1);
+    const int vrow = 4 * hf + ((lane & 15) >> 2);
+    vb0 = kKTile * 2 + vrow * 256 + 64 * (vrow & 3) + 16 * (d0 >> 3) + 2 * (d0 & 4);
+  }
 
   floatx16 oacc[4];
 #pragma unroll
@@ -231,88 +277,138 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   float m_run = -INFINITY;      // running max of the scaled logits (log2 domain), shared by both lane halves
   float l_run = 0.f;            // this lane's share of the running denominator
   const float k2 = kLog2e * 0.08838834764831845f;
+  floatx16 s_next = {0};        // logits of the next half-tile (32 tokens)
+  float alpha_pend = 1.f;       // rescale the accumulator still owes to the last change of the maximum
+  bf16x8 pf[2];                 // probabilities of the previous half-tile, as MFMA operands
+  pf[0] = pf[1] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
 
-  // per-lane offsets of the fragment reads
-  const int k_off = l32 * kKStride + 8 * hf;
-  // values: the lane addresses the 8-byte piece (token 4*hf + (lane%16)/4, elements d0 .. d0+3) where
-  // block q = 4*((lane/16)%2) + lane%4 of the 32-element slice starts at d0 = 16*(q%2) + 4*(q/2); after the
-  // transposing read lane (row i = lane%32) then holds four consecutive tokens of element
-  // 16*(i/4 % 2) + 4*(i/8) + i%4, which makes MFMA output row 8b + 4h + c element 16h + 4b + c
-  const int vq = 4 * ((lane >> 4) & 1) + (lane & 3);
-  const int v_off = (4 * hf + ((lane & 15) >> 2)) * kVStride + 16 * (vq & 1) + 4 * (vq >> 1);
-
-  gload(0);
-  swrite(0);
-  __syncthreads();
-  for (int t = 0; t < n_tiles; ++t) {
-    if (t + 1 < n_tiles) gload(t + 1);
-    const int kv0 = t * kBKV;
-    if (kv0 < wave_vis_max) {
-      const bf16_t* sK = sbase + (t & 1) * kStage;
-      const bf16_t* sV = sK + kKTile;
-      floatx16 sa = {0}, sb = {0};
-      const bf16_t* kp = sK + k_off;
+  // One pipeline step over half-tiles (32 tokens) h: the matrix unit computes the logits of half-tile
+  // h+1 and the P V product of half-tile h-1 while the vector unit does the softmax of half-tile h.
+  //   kaddr: kb0 + stage/half offset of the keys of h+1;  vaddr: vb0 + stage/half offset of the values
+  //   of h-1;  tok0: first token of half-tile h.
+  auto step = [&](auto do_s_c, auto do_sm_c, auto do_pv_c, auto mask_c, int kaddr, int vaddr, int tok0) {
+    constexpr bool DO_S = decltype(do_s_c)::value, DO_SM = decltype(do_sm_c)::value;
+    constexpr bool DO_PV = decltype(do_pv_c)::value, MASK = decltype(mask_c)::value;
+    // bring the accumulator (half-tiles < h-1) to the scale of the maximum the probabilities of
+    // half-tile h-1 were computed with; kept out of the main block so that block has no branch
+    if (__any(alpha_pend != 1.f)) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha_pend;
+    }
+    const floatx16 s_cur = s_next;
+    floatx16 s_new = {0};
+    if constexpr (DO_S) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + 16 * ks));
-        const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + 32 * kKStride + 16 * ks));
-        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], sa, 0, 0, 0);
-        sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], sb, 0, 0, 0);
+        const u32x4 f = *reinterpret_cast<const u32x4*>(smem + (kaddr ^ (32 * ks)));
+        s_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f), qf[ks], s_new, 0, 0, 0);
       }
-      // register v of sa is token kv0 + 8*(v/4) + 4*hf + v%4 (sb: + 32) against this lane's row
-      float p[32];
+    }
+    float alpha = 1.f;
+    bf16x8 pn[2];
+    if constexpr (DO_SM) {
+      // register v of s_cur is token tok0 + 8*(v/4) + 4*hf + v%4 against this lane's row
+      float p[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { p[v] = sa[v]; p[16 + v] = sb[v]; }
-      if (kv0 + kBKV > wave_vis_min) {
+      for (int v = 0; v < 16; ++v) p[v] = s_cur[v];
+      if constexpr (MASK) {
 #pragma unroll
-        for (int v = 0; v < 32; ++v) {
-          const int j = kv0 + 32 * (v >> 4) + 8 * ((v & 15) >> 2) + 4 * hf + (v & 3);
+        for (int v = 0; v < 16; ++v) {
+          const int j = tok0 + 8 * (v >> 2) + 4 * hf + (v & 3);
           p[v] = (j < vis) ? p[v] : -INFINITY;
         }
       }
       float mx = p[0];
 #pragma unroll
-      for (int v = 1; v < 32; ++v) mx = fmaxf(mx, p[v]);
+      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, p[v]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m_run, mx * k2);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+      alpha = __builtin_amdgcn_exp2f(m_run - m_use);
       float sum = 0.f;
 #pragma unroll
-      for (int v = 0; v < 32; ++v) {
+      for (int v = 0; v < 16; ++v) {
         p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(p[v], k2, -m_use));
         sum += p[v];
       }
       l_run = l_run * alpha + sum;
       m_run = m_new;
-      if (__any(alpha != 1.f)) {
+      // P^T fragments: k-step s uses registers 8*s .. 8*s+7 (tokens 16*s + 8*(e/4) + 4*hf + e%4)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
-      }
-      // P^T fragments: step s = 2*mt + t' uses registers 8*s .. 8*s+7 (tokens 16*s + 8*(e/4) + 4*hf + e%4)
-      bf16x8 pf[4];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
+      for (int s = 0; s < 2; ++s) {
         const u32x4 pk = mk4(cvt_pk_bf16(p[8 * s + 0], p[8 * s + 1]), cvt_pk_bf16(p[8 * s + 2], p[8 * s + 3]),
                              cvt_pk_bf16(p[8 * s + 4], p[8 * s + 5]), cvt_pk_bf16(p[8 * s + 6], p[8 * s + 7]));
-        pf[s] = __builtin_bit_cast(bf16x8, pk);
-      }
-      const bf16_t* vp = sV + v_off;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const shortx4 lo = lds_read_tr(vp + (16 * s) * kVStride + 32 * dt);
-          const shortx4 hi = lds_read_tr(vp + (16 * s + 8) * kVStride + 32 * dt);
-          const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[s], oacc[dt], 0, 0, 0);
-        }
+        pn[s] = __builtin_bit_cast(bf16x8, pk);
       }
     }
-    if (t + 1 < n_tiles) swrite((t + 1) & 1);
+    if constexpr (DO_PV) {
+#pragma unroll
+      for (int idx = 0; idx < 8; ++idx) {
+        const int s = idx >> 2, dt = idx & 3;
+        const unsigned char* vp = smem + (vaddr ^ (64 * dt)) + (16 * s) * 256;
+        const shortx4 lo = lds_read_tr(vp);
+        const shortx4 hi = lds_read_tr(vp + 8 * 256);
+        const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[s], oacc[dt], 0, 0, 0);
+      }
+    }
+    if constexpr (DO_S && DO_SM && DO_PV) {
+      // interleave: one MFMA, its LDS reads, and a share of the softmax arithmetic, 16 times
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < 10) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+      }
+    }
+    alpha_pend = alpha;
+    if constexpr (DO_SM) {
+      pf[0] = pn[0];
+      pf[1] = pn[1];
+    }
+    if constexpr (DO_S) s_next = s_new;
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+  auto dispatch = [&](bool do_s, bool do_sm, bool do_pv, bool mask, int kaddr, int vaddr, int tok0) {
+    if (do_s && do_sm && do_pv) {
+      if (mask) step(T_{}, T_{}, T_{}, T_{}, kaddr, vaddr, tok0); else step(T_{}, T_{}, T_{}, F_{}, kaddr, vaddr, tok0);
+    } else if (do_s && do_sm) {
+      if (mask) step(T_{}, T_{}, F_{}, T_{}, kaddr, vaddr, tok0); else step(T_{}, T_{}, F_{}, F_{}, kaddr, vaddr, tok0);
+    } else if (do_s) {
+      step(T_{}, F_{}, F_{}, F_{}, kaddr, vaddr, tok0);
+    } else if (do_sm && do_pv) {
+      if (mask) step(F_{}, T_{}, T_{}, T_{}, kaddr, vaddr, tok0); else step(F_{}, T_{}, T_{}, F_{}, kaddr, vaddr, tok0);
+    } else if (do_sm) {
+      if (mask) step(F_{}, T_{}, F_{}, T_{}, kaddr, vaddr, tok0); else step(F_{}, T_{}, F_{}, F_{}, kaddr, vaddr, tok0);
+    } else if (do_pv) {
+      step(F_{}, F_{}, T_{}, F_{}, kaddr, vaddr, tok0);
+    }
+  };
+
+  // Iteration t covers pipeline steps h = 2t-1 and 2t: they read the keys of tile t (stage t%2) and the
+  // values of tile t-1 (stage (t-1)%2) while the keys of tile t+1 and the values of tile t are in
+  // flight; one barrier per iteration orders the asynchronous loads against the reads.
+  const int n_half = (wave_vis_max + 31) / 32;          // half-tiles this wave works on
+  for (int t = 0; t <= n_tiles; ++t) {
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    if (t + 1 < n_tiles) aload_k(t + 1, (t + 1) & 1);
+    if (t < n_tiles) aload_v(t, t & 1);
+    const int kst = (t & 1) * (kStage * 2), vst = ((t + 1) & 1) * (kStage * 2);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int h = 2 * t - 1 + u;
+      const bool do_s = h + 1 < n_half;                       // h + 1 >= 0 always
+      const bool do_sm = h >= 0 && h < n_half;
+      const bool do_pv = h >= 1 && h - 1 < n_half;
+      const bool mask = (h + 1) * 32 > wave_vis_min;
+      // keys of half-tile h+1: rows 32*u of tile t; values of half-tile h-1: rows 32*u of tile t-1
+      dispatch(do_s, do_sm, do_pv, mask, kb0 + kst + u * 8192, vb0 + vst + u * 8192, h * 32);
+    }
   }
 
   // epilogue: output register v of tile dt is element 32*dt + 16*hf + v of this lane's row
