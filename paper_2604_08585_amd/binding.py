@@ -12,7 +12,8 @@ import torch
 from .inputs import LayerShape
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqcf.so")
+# QCF_LIB_PATH lets a developer load another build of the same library (A/B comparisons)
+LIB_PATH = os.environ.get("QCF_LIB_PATH") or os.path.join(_HERE, "libqcf.so")
 
 EXPORTS = [
     "qcf_status_string", "qcf_last_error", "qcf_version", "qcf_select_count",

@@ -215,7 +215,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   // Tokens past the end of the context are clamped (their probabilities are zero).
   const bf16_t* kg = static_cast<const bf16_t*>(a.k) + (c0 * a.Hkv + g) * 128;
   const bf16_t* vg = static_cast<const bf16_t*>(a.v) + (c0 * a.Hkv + g) * 128;
-  const int64_t kv_stride = (int64_t)a.Hkv * 128;
   const int ld_row = 4 * wave + (lane >> 4);                      // + 16*i
   const uint32_t row_bytes = (uint32_t)a.Hkv * 256u;              // one token row of the cache
   const uint32_t ld_kchunk = (uint32_t)(((lane & 15) ^ ld_row) * 16);           // row % 16 == ld_row
@@ -239,7 +238,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   auto aload_v = [&](int t, int st) {
     aload(vg, ld_voff, ld_vchunk, t, sbase + st * kStage + kKTile + (4 * wave) * 128);
   };
-  aload_k(0, 0);
+  auto aload2 = [&](int t, int st) { aload_k(t, st); aload_v(t, st); };
+  aload2(0, 0);
 
   // stationary query fragments: qf[ks] = row r, elements 16*ks + 8*hf .. +7
   bf16x8 qf[8];
@@ -253,22 +253,22 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     }
   }
 
-  // Per-lane byte addresses of the fragment reads inside a stage.
-  //  keys: token row l32, chunk 2*ks + hf lives in slot (2*ks + hf) ^ (l32 % 16); since 2*ks and hf
-  //  occupy different bits, the address of step ks is kb0 ^ (32 * ks).
-  const int kb0 = l32 * 256 + ((hf ^ (l32 & 15)) * 16);
-  //  values: the lane addresses the 8-byte piece (token 4*hf + (lane%16)/4, elements d0 .. d0+3) where
-  //  block q = 4*((lane/16)%2) + lane%4 of a 32-element slice starts at d0 = 16*(q%2) + 4*(q/2); after the
-  //  transposing read lane (row i = lane%32) holds four consecutive tokens of element
-  //  16*(i/4 % 2) + 4*(i/8) + i%4, which makes MFMA output row 8b + 4h + c element 16h + 4b + c.
-  //  Chunk 4*dt + d0/8 of row r lives in slot (4*dt + d0/8) ^ (4 * (r % 4)): the address of output tile
-  //  dt is vb0 ^ (64 * dt).
-  int vb0;
+  // per-lane byte offsets of the fragment reads inside a stage
+  int kofs[8];     // key fragment ks: token row l32 (+32), chunk 2*ks + hf
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) kofs[ks] = l32 * 256 + (((2 * ks + hf) ^ (l32 & 15)) * 16);
+  // values: the lane addresses the 8-byte piece (token 4*hf + (lane%16)/4, elements d0 .. d0+3) where
+  // block q = 4*((lane/16)%2) + lane%4 of a 32-element slice starts at d0 = 16*(q%2) + 4*(q/2); after the
+  // transposing read lane (row i = lane%32) holds four consecutive tokens of element
+  // 16*(i/4 % 2) + 4*(i/8) + i%4, which makes MFMA output row 8b + 4h + c element 16h + 4b + c
+  int vofs[4];     // value fragment of output tile dt
   {
     const int vq = 4 * ((lane >> 4) & 1) + (lane & 3);
     const int d0 = 16 * (vq & 1) + 4 * (vq >> 1);
     const int vrow = 4 * hf + ((lane & 15) >> 2);
-    vb0 = kKTile * 2 + vrow * 256 + 64 * (vrow & 3) + 16 * (d0 >> 3) + 2 * (d0 & 4);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+      vofs[dt] = kKTile * 2 + vrow * 256 + (((4 * dt + d0 / 8) ^ (4 * (vrow & 3))) * 16) + (d0 & 4) * 2;
   }
 
   floatx16 oacc[4];
@@ -277,138 +277,90 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   float m_run = -INFINITY;      // running max of the scaled logits (log2 domain), shared by both lane halves
   float l_run = 0.f;            // this lane's share of the running denominator
   const float k2 = kLog2e * 0.08838834764831845f;
-  floatx16 s_next = {0};        // logits of the next half-tile (32 tokens)
-  float alpha_pend = 1.f;       // rescale the accumulator still owes to the last change of the maximum
-  bf16x8 pf[2];                 // probabilities of the previous half-tile, as MFMA operands
-  pf[0] = pf[1] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
 
-  // One pipeline step over half-tiles (32 tokens) h: the matrix unit computes the logits of half-tile
-  // h+1 and the P V product of half-tile h-1 while the vector unit does the softmax of half-tile h.
-  //   kaddr: kb0 + stage/half offset of the keys of h+1;  vaddr: vb0 + stage/half offset of the values
-  //   of h-1;  tok0: first token of half-tile h.
-  auto step = [&](auto do_s_c, auto do_sm_c, auto do_pv_c, auto mask_c, int kaddr, int vaddr, int tok0) {
-    constexpr bool DO_S = decltype(do_s_c)::value, DO_SM = decltype(do_sm_c)::value;
-    constexpr bool DO_PV = decltype(do_pv_c)::value, MASK = decltype(mask_c)::value;
-    // bring the accumulator (half-tiles < h-1) to the scale of the maximum the probabilities of
-    // half-tile h-1 were computed with; kept out of the main block so that block has no branch
-    if (__any(alpha_pend != 1.f)) {
+  auto process = [&](const unsigned char* stage, int kv0) {
+    floatx16 sa = {0}, sb = {0};
+    {
+      u32x4 fa[2], fb[2];
+      fa[0] = *reinterpret_cast<const u32x4*>(stage + kofs[0]);
+      fb[0] = *reinterpret_cast<const u32x4*>(stage + kofs[0] + 32 * 256);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        if (ks < 7) {
+          fa[(ks + 1) & 1] = *reinterpret_cast<const u32x4*>(stage + kofs[ks + 1]);
+          fb[(ks + 1) & 1] = *reinterpret_cast<const u32x4*>(stage + kofs[ks + 1] + 32 * 256);
+        }
+        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[ks & 1]), qf[ks], sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[ks & 1]), qf[ks], sb, 0, 0, 0);
+      }
+    }
+    // first value fragments can travel while the softmax runs
+    shortx4 vlo[2], vhi[2];
+    vlo[0] = lds_read_tr(stage + vofs[0]);
+    vhi[0] = lds_read_tr(stage + vofs[0] + 8 * 256);
+    // register v of sa is token kv0 + 8*(v/4) + 4*hf + v%4 (sb: + 32) against this lane's row
+    float p[32];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { p[v] = sa[v]; p[16 + v] = sb[v]; }
+    if (kv0 + kBKV > wave_vis_min) {
+#pragma unroll
+      for (int v = 0; v < 32; ++v) {
+        const int j = kv0 + 32 * (v >> 4) + 8 * ((v & 15) >> 2) + 4 * hf + (v & 3);
+        p[v] = (j < vis) ? p[v] : -INFINITY;
+      }
+    }
+    float mx = p[0];
+#pragma unroll
+    for (int v = 1; v < 32; ++v) mx = fmaxf(mx, p[v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx * k2);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+    float sum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 32; ++v) {
+      p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(p[v], k2, -m_use));
+      sum += p[v];
+    }
+    l_run = l_run * alpha + sum;
+    m_run = m_new;
+    if (__any(alpha != 1.f)) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha_pend;
+        for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
     }
-    const floatx16 s_cur = s_next;
-    floatx16 s_new = {0};
-    if constexpr (DO_S) {
+    // P^T fragments: step s = 2*mt + t' uses registers 8*s .. 8*s+7 (tokens 16*s + 8*(e/4) + 4*hf + e%4)
+    bf16x8 pf[4];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const u32x4 f = *reinterpret_cast<const u32x4*>(smem + (kaddr ^ (32 * ks)));
-        s_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f), qf[ks], s_new, 0, 0, 0);
-      }
+    for (int s = 0; s < 4; ++s) {
+      const u32x4 pk = mk4(cvt_pk_bf16(p[8 * s + 0], p[8 * s + 1]), cvt_pk_bf16(p[8 * s + 2], p[8 * s + 3]),
+                           cvt_pk_bf16(p[8 * s + 4], p[8 * s + 5]), cvt_pk_bf16(p[8 * s + 6], p[8 * s + 7]));
+      pf[s] = __builtin_bit_cast(bf16x8, pk);
     }
-    float alpha = 1.f;
-    bf16x8 pn[2];
-    if constexpr (DO_SM) {
-      // register v of s_cur is token tok0 + 8*(v/4) + 4*hf + v%4 against this lane's row
-      float p[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) p[v] = s_cur[v];
-      if constexpr (MASK) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int j = tok0 + 8 * (v >> 2) + 4 * hf + (v & 3);
-          p[v] = (j < vis) ? p[v] : -INFINITY;
-        }
+    for (int idx = 0; idx < 16; ++idx) {
+      const int s = idx >> 2, dt = idx & 3;
+      if (idx < 15) {
+        const int s2 = (idx + 1) >> 2, dt2 = (idx + 1) & 3;
+        vlo[(idx + 1) & 1] = lds_read_tr(stage + vofs[dt2] + (16 * s2) * 256);
+        vhi[(idx + 1) & 1] = lds_read_tr(stage + vofs[dt2] + (16 * s2 + 8) * 256);
       }
-      float mx = p[0];
-#pragma unroll
-      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, p[v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx * k2);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-      float sum = 0.f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(p[v], k2, -m_use));
-        sum += p[v];
-      }
-      l_run = l_run * alpha + sum;
-      m_run = m_new;
-      // P^T fragments: k-step s uses registers 8*s .. 8*s+7 (tokens 16*s + 8*(e/4) + 4*hf + e%4)
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const u32x4 pk = mk4(cvt_pk_bf16(p[8 * s + 0], p[8 * s + 1]), cvt_pk_bf16(p[8 * s + 2], p[8 * s + 3]),
-                             cvt_pk_bf16(p[8 * s + 4], p[8 * s + 5]), cvt_pk_bf16(p[8 * s + 6], p[8 * s + 7]));
-        pn[s] = __builtin_bit_cast(bf16x8, pk);
-      }
-    }
-    if constexpr (DO_PV) {
-#pragma unroll
-      for (int idx = 0; idx < 8; ++idx) {
-        const int s = idx >> 2, dt = idx & 3;
-        const unsigned char* vp = smem + (vaddr ^ (64 * dt)) + (16 * s) * 256;
-        const shortx4 lo = lds_read_tr(vp);
-        const shortx4 hi = lds_read_tr(vp + 8 * 256);
-        const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[s], oacc[dt], 0, 0, 0);
-      }
-    }
-    if constexpr (DO_S && DO_SM && DO_PV) {
-      // interleave: one MFMA, its LDS reads, and a share of the softmax arithmetic, 16 times
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i < 10) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
-      }
-    }
-    alpha_pend = alpha;
-    if constexpr (DO_SM) {
-      pf[0] = pn[0];
-      pf[1] = pn[1];
-    }
-    if constexpr (DO_S) s_next = s_new;
-  };
-  using T_ = std::true_type;
-  using F_ = std::false_type;
-  auto dispatch = [&](bool do_s, bool do_sm, bool do_pv, bool mask, int kaddr, int vaddr, int tok0) {
-    if (do_s && do_sm && do_pv) {
-      if (mask) step(T_{}, T_{}, T_{}, T_{}, kaddr, vaddr, tok0); else step(T_{}, T_{}, T_{}, F_{}, kaddr, vaddr, tok0);
-    } else if (do_s && do_sm) {
-      if (mask) step(T_{}, T_{}, F_{}, T_{}, kaddr, vaddr, tok0); else step(T_{}, T_{}, F_{}, F_{}, kaddr, vaddr, tok0);
-    } else if (do_s) {
-      step(T_{}, F_{}, F_{}, F_{}, kaddr, vaddr, tok0);
-    } else if (do_sm && do_pv) {
-      if (mask) step(F_{}, T_{}, T_{}, T_{}, kaddr, vaddr, tok0); else step(F_{}, T_{}, T_{}, F_{}, kaddr, vaddr, tok0);
-    } else if (do_sm) {
-      if (mask) step(F_{}, T_{}, F_{}, T_{}, kaddr, vaddr, tok0); else step(F_{}, T_{}, F_{}, F_{}, kaddr, vaddr, tok0);
-    } else if (do_pv) {
-      step(F_{}, F_{}, T_{}, F_{}, kaddr, vaddr, tok0);
+      const shortx8 both = __builtin_shufflevector(vlo[idx & 1], vhi[idx & 1], 0, 1, 2, 3, 4, 5, 6, 7);
+      oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[s], oacc[dt], 0, 0, 0);
     }
   };
 
-  // Iteration t covers pipeline steps h = 2t-1 and 2t: they read the keys of tile t (stage t%2) and the
-  // values of tile t-1 (stage (t-1)%2) while the keys of tile t+1 and the values of tile t are in
-  // flight; one barrier per iteration orders the asynchronous loads against the reads.
-  const int n_half = (wave_vis_max + 31) / 32;          // half-tiles this wave works on
-  for (int t = 0; t <= n_tiles; ++t) {
+  for (int t = 0; t < n_tiles; t += 2) {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();                                  // tile t has landed; stage 1 is free again
+    if (t + 1 < n_tiles) aload2(t + 1, 1);
+    if (t * kBKV < wave_vis_max) process(smem, t * kBKV);
+    if (t + 1 >= n_tiles) break;
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (t + 1 < n_tiles) aload_k(t + 1, (t + 1) & 1);
-    if (t < n_tiles) aload_v(t, t & 1);
-    const int kst = (t & 1) * (kStage * 2), vst = ((t + 1) & 1) * (kStage * 2);
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int h = 2 * t - 1 + u;
-      const bool do_s = h + 1 < n_half;                       // h + 1 >= 0 always
-      const bool do_sm = h >= 0 && h < n_half;
-      const bool do_pv = h >= 1 && h - 1 < n_half;
-      const bool mask = (h + 1) * 32 > wave_vis_min;
-      // keys of half-tile h+1: rows 32*u of tile t; values of half-tile h-1: rows 32*u of tile t-1
-      dispatch(do_s, do_sm, do_pv, mask, kb0 + kst + u * 8192, vb0 + vst + u * 8192, h * 32);
-    }
+    if (t + 2 < n_tiles) aload2(t + 2, 0);
+    if ((t + 1) * kBKV < wave_vis_max) process(smem + (size_t)kStage * 2, (t + 1) * kBKV);
   }
 
   // epilogue: output register v of tile dt is element 32*dt + 16*hf + v of this lane's row
