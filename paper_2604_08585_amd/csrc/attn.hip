@@ -112,8 +112,6 @@ __global__ __launch_bounds__(256) void attn_generic(AttnArgs a) {
 
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef short shortx8 __attribute__((ext_vector_type(8)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBKV = 64;                    // tokens per K/V tile
 constexpr int kKTile = kBKV * 128;          // bf16 elements; rows are 256 B, no padding (swizzled instead)
@@ -122,33 +120,11 @@ constexpr int kStage = kKTile + kVTile;
 constexpr size_t kAttnLds = (size_t)2 * kStage * 2;
 constexpr int kRowsPerWg = 128;             // (selected row, head-in-group) pairs per workgroup
 
-__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
-  const floatx2 f = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
-}
-
 // LDS transposing read: within each group of 16 lanes, lane i receives element i%4 of the four
 // 8-byte rows addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4 of the group.
 __device__ __forceinline__ shortx4 lds_read_tr(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
       (shortx4 __attribute__((address_space(3)))*)(const_cast<unsigned char*>(p)));
-}
-
-// 16 bytes per lane from global memory straight into LDS: lane L lands at lds + 16*L.  Issued through
-// inline assembly so that the compiler does not count it among the loads it waits for before LDS
-// reads: the kernel waits for these loads itself, once per tile, just before the barrier.
-__device__ __forceinline__ void load_to_lds(const void* base, uint32_t lane_off, bf16_t* lds) {
-  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(lds));
-  const uint64_t b = (uint64_t)(uintptr_t)base;     // wave-uniform: goes to a scalar register pair
-  // the builtin returns a signed int: widen through uint32_t, or a low half >= 2^31 would smear ones
-  // over the high half of the address
-  const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
-                      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(lane_off), "s"(sb), "s"(lds_addr)
-               : "memory", "m0");
 }
 
 // Tile layouts in LDS (rows of 256 bytes = 16 chunks of 16 bytes, no padding):

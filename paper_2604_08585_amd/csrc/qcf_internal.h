@@ -89,6 +89,46 @@ template <> struct Vec16<bf16_t> {
   }
 };
 
+// ---- gfx950 helpers shared by the MFMA kernels ---------------------------------------
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round-to-nearest-even in hardware (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  const floatx2_t f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void* lds) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(const_cast<void*>(lds));
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane L lands at lds + 16*L (lds is
+// wave-uniform).  Issued through inline assembly so that the compiler does not count these among the
+// loads it waits for before unrelated LDS reads: callers wait for them themselves
+// (__builtin_amdgcn_s_waitcnt(0)) before the barrier that publishes the tile.
+// Form 1: wave-uniform 64-bit base in scalar registers plus a 32-bit byte offset per lane.
+__device__ __forceinline__ void load_to_lds(const void* base, uint32_t lane_off, void* lds) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((int)lds_offset_of(lds));
+  const uint64_t b = (uint64_t)(uintptr_t)base;
+  // the builtin returns a signed int: widen through uint32_t, or a low half >= 2^31 would smear ones
+  // over the high half of the address
+  const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
+                      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_off), "s"(sb), "s"(lds_addr)
+               : "memory", "m0");
+}
+// Form 2: a full 64-bit address per lane.
+__device__ __forceinline__ void load_to_lds_addr(const void* gptr, void* lds) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((int)lds_offset_of(lds));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+
 // ---- launchers (one per translation unit) --------------------------------------
 // Each returns QCF_OK or an error after enqueueing on `st`; arguments were validated
 // by the entry points in api.hip.

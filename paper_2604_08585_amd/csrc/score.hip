@@ -102,7 +102,7 @@ constexpr int kTokPerWave = 64;                 // tokens a wave keeps stationar
 constexpr int kWavesPerWg = 4;
 constexpr int kTokPerWg = kTokPerWave * kWavesPerWg;
 constexpr int kRowBlock = 320;                  // probe rows (of one group) staged in LDS at a time
-constexpr int kQStride = 128 + 8;               // bf16 elements per staged row (16-byte pad)
+constexpr int kQStride = 128;                   // bf16 elements per staged row (swizzled, no padding)
 
 struct ScoreArgs {
   const bf16_t* q;            // [total_probe, H, 128]
@@ -159,25 +159,24 @@ __device__ __forceinline__ void load_k_frags(const ScoreArgs& a, int64_t c0, int
 }
 
 // Stages probe rows [r_begin, r_begin + n_rows) of group g (row r = i*G + hh <-> probe row i,
-// head g*G + hh) into LDS, zero-filling up to a multiple of 32 rows.
-__device__ __forceinline__ void stage_q(const ScoreArgs& a, int64_t p0, int g, int r_begin, int n_rows,
-                                        int n_rows_pad, bf16_t* sQ, int tid) {
-  for (int idx = tid; idx < n_rows_pad * 16; idx += kWavesPerWg * 64) {
-    const int r = idx >> 4, c = idx & 15;
-    u32x4 v = u32x4{0u, 0u, 0u, 0u};
-    if (r < n_rows) {
-      const int rr = r_begin + r;
-      const int i = rr / a.G, hh = rr - i * a.G;
-      v = *reinterpret_cast<const u32x4*>(a.q + ((p0 + i) * a.H + g * a.G + hh) * 128 + c * 8);
-    }
-    *reinterpret_cast<u32x4*>(sQ + r * kQStride + c * 8) = v;
+// head g*G + hh) into LDS with asynchronous direct-to-LDS loads; the caller waits and synchronises.
+// Staged rows are 256 bytes (16 chunks of 16 bytes) without padding; chunk c of row r sits in slot
+// c ^ (r % 16), so the 16-byte fragment reads of 16 consecutive rows touch 16 different bank groups.
+// Rows up to the next multiple of 32 are filled with a copy of the last row (never used in a result).
+__device__ __forceinline__ void stage_q_async(const ScoreArgs& a, int64_t p0, int g, int r_begin, int n_rows,
+                                              int n_rows_pad, unsigned char* sQ, int wave, int lane) {
+  for (int j = wave; j < n_rows_pad / 4; j += kWavesPerWg) {       // one 1 KB instruction = 4 rows
+    const int r = 4 * j + (lane >> 4);
+    const int rr = r_begin + min(r, n_rows - 1);
+    const int i = rr / a.G, hh = rr - i * a.G;
+    const int chunk = (lane & 15) ^ (r & 15);
+    load_to_lds_addr(a.q + ((p0 + i) * a.H + g * a.G + hh) * 128 + chunk * 8, sQ + j * 1024);
   }
 }
 
 template <bool LIMIT>
 __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  bf16_t* sQ = reinterpret_cast<bf16_t*>(smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = blockIdx.y;
   int b, T, tile_tok0, slice0;
@@ -189,6 +188,8 @@ __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
   const int tok0 = tile_tok0 + wave * kTokPerWave;
   const bool wave_active = tok0 < T;
   const float k2 = kLog2e * 0.08838834764831845f;   // log2(e) / sqrt(128)
+  // byte offset of this lane's fragment (row lane%32, chunk 2*ks + lane/32) is qb0 ^ (32 * ks)
+  const int qb0 = (lane & 31) * 256 + (((lane >> 5) ^ (lane & 15)) * 16);
 
   bf16x8 kf[2][8];
   load_k_frags(a, c0, T, tok0, g, lane, kf);
@@ -198,15 +199,16 @@ __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
     const int n_rows = min(kRowBlock, rows - r_begin);
     const int n_pad = (n_rows + 31) & ~31;
     __syncthreads();
-    stage_q(a, p0, g, r_begin, n_rows, n_pad, sQ, tid);
+    stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (!wave_active) continue;
     for (int rt = 0; rt < n_pad; rt += 32) {
       floatx16 acc0 = {0}, acc1 = {0};
-      const bf16_t* qrow = sQ + (rt + (lane & 31)) * kQStride + 8 * (lane >> 5);
+      const unsigned char* qrow = smem + rt * 256;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 qf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + 16 * ks));
+        const bf16x8 qf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + (qb0 ^ (32 * ks))));
         // S^T tile: rows = tokens (A = keys), columns = probe rows (B = queries)
         acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf, acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf, acc1, 0, 0, 0);
@@ -239,40 +241,58 @@ __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
   }
 }
 
-// one thread per (probe row, head): log2-sum-exp over the request's slices
+// log2-sum-exp over the request's slices for every (probe row, head): a workgroup handles 16
+// (row, head) pairs; 16 threads per pair fold every 16th slice, then one thread folds the 16
+// partial results in a fixed order (deterministic).
 __global__ __launch_bounds__(256) void score_combine(ScoreArgs a) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= a.total_probe * a.H) return;
-  const int64_t row = idx / a.H;
-  const int b = find_request(a.probe_off, a.B, row);
-  if (b >= a.B) return;
-  int slice0 = 0;
-  int T = 0;
-  for (int bb = 0; bb <= b; ++bb) {
-    const int64_t c0 = min(max(a.ctx_off[bb], (int64_t)0), a.total_ctx);
-    const int64_t c1 = min(max(a.ctx_off[bb + 1], c0), a.total_ctx);
-    T = (int)(c1 - c0);
-    if (bb < b) slice0 += ((T + kTokPerWg - 1) / kTokPerWg) * kWavesPerWg;
-  }
-  const int n_slices = (T + kTokPerWave - 1) / kTokPerWave;
-  float m = -INFINITY;
-  for (int s = 0; s < n_slices; ++s)
-    m = fmaxf(m, a.part[(int64_t)(slice0 + s) * (a.total_probe * a.H) + idx].x);
-  float z = 0.f;
-  if (m > -INFINITY) {
-    for (int s = 0; s < n_slices; ++s) {
-      const float2 p = a.part[(int64_t)(slice0 + s) * (a.total_probe * a.H) + idx];
-      if (p.x > -INFINITY) z += p.y * exp2f(p.x - m);
+  __shared__ float sm[16][17], sz[16][17];
+  const int il = threadIdx.x & 15, sg = threadIdx.x >> 4;
+  const int64_t total = a.total_probe * a.H;
+  const int64_t idx = (int64_t)blockIdx.x * 16 + il;
+  float m = -INFINITY, z = 0.f;
+  if (idx < total) {
+    const int64_t row = idx / a.H;
+    const int b = find_request(a.probe_off, a.B, row);
+    if (b < a.B) {
+      int slice0 = 0, T = 0;
+      for (int bb = 0; bb <= b; ++bb) {
+        const int64_t c0 = min(max(a.ctx_off[bb], (int64_t)0), a.total_ctx);
+        const int64_t c1 = min(max(a.ctx_off[bb + 1], c0), a.total_ctx);
+        T = (int)(c1 - c0);
+        if (bb < b) slice0 += ((T + kTokPerWg - 1) / kTokPerWg) * kWavesPerWg;
+      }
+      const int n_slices = (T + kTokPerWave - 1) / kTokPerWave;
+      for (int s = sg; s < n_slices; s += 16) {
+        const float2 p = a.part[(int64_t)(slice0 + s) * total + idx];
+        if (p.x > -INFINITY) {
+          const float mn = fmaxf(m, p.x);
+          z = z * exp2f(m - mn) + p.y * exp2f(p.x - mn);
+          m = mn;
+        }
+      }
     }
   }
-  // rows that see nothing get +inf so that exp2(logit - lse) is 0
-  a.lse2[idx] = (z > 0.f) ? m + log2f(z) : INFINITY;
+  sm[il][sg] = m;
+  sz[il][sg] = z;
+  __syncthreads();
+  if (sg == 0 && idx < total) {
+    float mm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) mm = fmaxf(mm, sm[il][j]);
+    float zz = 0.f;
+    if (mm > -INFINITY) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (sm[il][j] > -INFINITY) zz += sz[il][j] * exp2f(sm[il][j] - mm);
+    }
+    // rows that see nothing get +inf so that exp2(logit - lse) is 0
+    a.lse2[idx] = (zz > 0.f) ? mm + log2f(zz) : INFINITY;
+  }
 }
 
 template <bool LIMIT>
 __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  bf16_t* sQ = reinterpret_cast<bf16_t*>(smem);
   float* sL = reinterpret_cast<float*>(smem + (size_t)kRowBlock * kQStride * 2);   // [kRowBlock] lse2
   int* sLim = reinterpret_cast<int*>(sL + kRowBlock);                                // [kRowBlock]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -286,6 +306,7 @@ __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
   const int tok0 = tile_tok0 + wave * kTokPerWave;
   const bool wave_active = tok0 < T;
   const float k2 = kLog2e * 0.08838834764831845f;
+  const int qb0 = (lane & 31) * 256 + (((lane >> 5) ^ (lane & 15)) * 16);
 
   bf16x8 kf[2][8];
   load_k_frags(a, c0, T, tok0, g, lane, kf);
@@ -295,7 +316,7 @@ __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
     const int n_rows = min(kRowBlock, rows - r_begin);
     const int n_pad = (n_rows + 31) & ~31;
     __syncthreads();
-    stage_q(a, p0, g, r_begin, n_rows, n_pad, sQ, tid);
+    stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
     for (int r = tid; r < n_pad; r += 256) {
       float l = INFINITY;
       int lim = 0;
@@ -308,14 +329,15 @@ __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
       sL[r] = l;
       sLim[r] = lim;
     }
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (!wave_active) continue;
     for (int rt = 0; rt < n_pad; rt += 32) {
       floatx16 acc0 = {0}, acc1 = {0};
-      const bf16_t* qrow = sQ + (rt + (lane & 31)) * kQStride + 8 * (lane >> 5);
+      const unsigned char* qrow = smem + rt * 256;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 qf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + 16 * ks));
+        const bf16x8 qf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + (qb0 ^ (32 * ks))));
         // S tile: rows = probe rows (A = queries), columns = tokens (B = keys)
         acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[0][ks], acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[1][ks], acc1, 0, 0, 0);
@@ -472,7 +494,7 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
     if (probe_limit) score_pass1<true><<<grid, block, kPass1Lds, st>>>(a);
     else score_pass1<false><<<grid, block, kPass1Lds, st>>>(a);
     QCF_TRY_LAUNCH("score pass 1");
-    score_combine<<<dim3((unsigned)((total_probe * H + 255) / 256)), dim3(256), 0, st>>>(a);
+    score_combine<<<dim3((unsigned)((total_probe * H + 15) / 16)), dim3(256), 0, st>>>(a);
     QCF_TRY_LAUNCH("score combine");
     if (probe_limit) score_pass2<true><<<grid, block, kPass2Lds, st>>>(a);
     else score_pass2<false><<<grid, block, kPass2Lds, st>>>(a);
