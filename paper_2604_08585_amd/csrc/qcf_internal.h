@@ -106,7 +106,8 @@ __device__ __forceinline__ uint32_t lds_offset_of(const void* lds) {
 // 16 bytes per lane from global memory straight into LDS: lane L lands at lds + 16*L (lds is
 // wave-uniform).  Issued through inline assembly so that the compiler does not count these among the
 // loads it waits for before unrelated LDS reads: callers wait for them themselves
-// (__builtin_amdgcn_s_waitcnt(0)) before the barrier that publishes the tile.
+// (__builtin_amdgcn_s_waitcnt(0)) before the barrier that publishes the tile.  M0 (the LDS base of
+// such a load) is saved and restored around the instruction.
 // Form 1: wave-uniform 64-bit base in scalar registers plus a 32-bit byte offset per lane.
 __device__ __forceinline__ void load_to_lds(const void* base, uint32_t lane_off, void* lds) {
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((int)lds_offset_of(lds));
@@ -115,18 +116,20 @@ __device__ __forceinline__ void load_to_lds(const void* base, uint32_t lane_off,
   // over the high half of the address
   const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
                       (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
                : "v"(lane_off), "s"(sb), "s"(lds_addr)
-               : "memory", "m0");
+               : "memory");
 }
 // Form 2: a full 64-bit address per lane.
 __device__ __forceinline__ void load_to_lds_addr(const void* gptr, void* lds) {
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((int)lds_offset_of(lds));
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
                : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
+               : "memory");
 }
 
 // ---- launchers (one per translation unit) --------------------------------------

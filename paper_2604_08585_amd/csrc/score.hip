@@ -218,20 +218,23 @@ __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
       int lim = T;
       if (LIMIT && r < rows) lim = min(T, max(0, a.probe_limit[p0 + r / a.G]));
       float s[32];
-      float mx = -INFINITY;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int t0 = tok0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        s[v] = (t0 < lim) ? acc0[v] * k2 : -INFINITY;
-        s[16 + v] = (t0 + 32 < lim) ? acc1[v] * k2 : -INFINITY;
-        mx = fmaxf(mx, fmaxf(s[v], s[16 + v]));
+      for (int v = 0; v < 16; ++v) { s[v] = acc0[v]; s[16 + v] = acc1[v]; }
+      if (LIMIT || tok0 + kTokPerWave > T) {        // wave-uniform: only ragged or limited tiles compare
+#pragma unroll
+        for (int v = 0; v < 32; ++v) {
+          const int t0 = tok0 + 32 * (v >> 4) + 8 * ((v & 15) >> 2) + 4 * (lane >> 5) + (v & 3);
+          s[v] = (t0 < lim) ? s[v] : -INFINITY;
+        }
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float mx = s[0];
+#pragma unroll
+      for (int v = 1; v < 32; ++v) mx = fmaxf(mx, s[v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * k2;          // k2 > 0: scaling commutes with the maximum
+      const float m_use = (mx == -INFINITY) ? 0.f : mx;
       float sum = 0.f;
-      if (mx > -INFINITY) {
 #pragma unroll
-        for (int v = 0; v < 32; ++v) sum += exp2f(s[v] - mx);
-      }
+      for (int v = 0; v < 32; ++v) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], k2, -m_use));
       sum += __shfl_xor(sum, 32, 64);
       if (lane < 32 && r < rows) {
         const int i = r / a.G, hh = r - i * a.G;
@@ -358,8 +361,8 @@ __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int v = 4 * q4 + c;
-          float pa = exp2f(acc0[v] * k2 - ls[c]);
-          float pb = exp2f(acc1[v] * k2 - ls[c]);
+          float pa = __builtin_amdgcn_exp2f(__builtin_fmaf(acc0[v], k2, -ls[c]));
+          float pb = __builtin_amdgcn_exp2f(__builtin_fmaf(acc1[v], k2, -ls[c]));
           if (LIMIT) {
             if (tA >= lims[c]) pa = 0.f;
             if (tB >= lims[c]) pb = 0.f;
