@@ -120,10 +120,10 @@ __global__ __launch_bounds__(256) void qkv_rope_split_generic(const float* __res
 
 // ------------------------------------------------------------------ MFMA path (bf16)
 
-constexpr int kBK = 64;                  // contraction elements per LDS stage
-constexpr int kLdsStride = kBK + 8;      // bf16 elements per staged row (16-byte pad)
+constexpr int kBK = 64;                  // contraction elements per LDS stage (rows of 128 bytes)
 constexpr int kBN = 128;                 // output columns per workgroup (whole heads)
 constexpr int kCStride = kBN + 4;        // floats per row of the epilogue slab
+constexpr int kStages = 3;               // ring of LDS stages filled by asynchronous loads
 
 struct QkvArgs {
   const bf16_t* x;
@@ -141,23 +141,27 @@ template <int TM, int TN, int WGM, int WGN>
 struct Tile {
   static constexpr int BM = 32 * TM * WGM;
   static constexpr int NTHR = 64 * WGM * WGN;
-  static constexpr int A_CH = BM * (kBK / 8) / NTHR;     // 16-byte chunks per thread and stage
-  static constexpr int B_CH = kBN * (kBK / 8) / NTHR;
-  static constexpr int STAGE = (BM + kBN) * kLdsStride;   // bf16 elements per stage
-  static constexpr size_t LDS_MAIN = (size_t)2 * STAGE * 2;
+  static constexpr int NWAVE = WGM * WGN;
+  static constexpr int A_LD = BM / 8 / NWAVE;             // 1 KB load instructions per wave and stage
+  static constexpr int B_LD = kBN / 8 / NWAVE;
+  static constexpr int STAGE = (BM + kBN) * kBK * 2;      // bytes per stage
+  static constexpr size_t LDS_MAIN = (size_t)kStages * STAGE;
   static constexpr size_t LDS_EPI = (size_t)32 * TM * kCStride * 4;
   static constexpr size_t LDS = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
   static_assert(32 * TN * WGN == kBN, "a workgroup covers 128 output columns");
-  static_assert(BM * (kBK / 8) % NTHR == 0 && kBN * (kBK / 8) % NTHR == 0, "chunk split");
+  static_assert((BM / 8) % NWAVE == 0 && (kBN / 8) % NWAVE == 0, "load split");
 };
 
+// Staged tiles have rows of 128 bytes (8 chunks of 16 bytes) without padding; chunk c of row r sits in
+// slot c ^ ((r / 2) % 8), so the 16-byte fragment reads of 16 consecutive rows touch 16 different bank
+// groups.  One load instruction of a wave fills 8 rows (1 KB): lane L fills slot L%8 of row L/8.
 template <int TM, int TN, int WGM, int WGN, int STYLE>
 __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
   using C = Tile<TM, TN, WGM, WGN>;
   extern __shared__ __align__(16) unsigned char smem[];
-  bf16_t* sbase = reinterpret_cast<bf16_t*>(smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
+  const int hf = lane >> 5, l32 = lane & 31;
   const int64_t m0 = (int64_t)blockIdx.x * C::BM;
   const int col0 = blockIdx.y * kBN;
 
@@ -171,49 +175,45 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
   else { out = a.v; out_cols = kv_cols; out_col0 = col0 - q_cols - kv_cols; rotate = false; }
   if (!out) return;
 
-  int64_t a_off[C::A_CH], b_off[C::B_CH];
+  // load instruction i of this wave covers tile rows 8*(wave + NWAVE*i) .. +7
+  const int ld_r = lane >> 3;                                    // row inside the 8-row group
+  const bf16_t* a_src[C::A_LD];                                  // per-lane source of chunk (lane%8)^swz at k = 0
 #pragma unroll
-  for (int i = 0; i < C::A_CH; ++i) {
-    const int chunk = tid + i * C::NTHR;
-    const int row = chunk >> 3, c = chunk & 7;
-    a_off[i] = -1;
+  for (int i = 0; i < C::A_LD; ++i) {
+    const int row = 8 * (wave + C::NWAVE * i) + ld_r;
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
     const int64_t m = m0 + row;
+    int64_t idx = 0;                                             // rows past M read row 0; never stored
     if (m < a.M) {
-      const int64_t idx = a.gather ? (int64_t)a.gather[m] : m;
-      if (idx >= 0 && idx < a.x_rows) a_off[i] = idx * a.d_model + c * 8;
+      idx = a.gather ? (int64_t)a.gather[m] : m;
+      if (idx < 0 || idx >= a.x_rows) idx = 0;                   // stored as zeros in the epilogue
     }
+    a_src[i] = a.x + idx * a.d_model + chunk * 8;
   }
+  uint32_t b_off[C::B_LD];                                       // byte offset from w + col0 * d_model
 #pragma unroll
-  for (int i = 0; i < C::B_CH; ++i) {
-    const int chunk = tid + i * C::NTHR;
-    const int row = chunk >> 3, c = chunk & 7;
-    b_off[i] = (int64_t)(col0 + row) * a.d_model + c * 8;
+  for (int i = 0; i < C::B_LD; ++i) {
+    const int row = 8 * (wave + C::NWAVE * i) + ld_r;
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+    b_off[i] = (uint32_t)row * (uint32_t)a.d_model * 2u + (uint32_t)chunk * 16u;
   }
-  u32x4 ra[C::A_CH], rb[C::B_CH];
-  auto gload = [&](int kt) {
+  const char* b_base = reinterpret_cast<const char*>(a.w + (int64_t)col0 * a.d_model);
+  auto issue = [&](int kt, int st) {
+    unsigned char* sA = smem + (size_t)st * C::STAGE;
+    unsigned char* sB = sA + C::BM * kBK * 2;
 #pragma unroll
-    for (int i = 0; i < C::A_CH; ++i) {
-      ra[i] = u32x4{0u, 0u, 0u, 0u};
-      if (a_off[i] >= 0) ra[i] = *reinterpret_cast<const u32x4*>(a.x + a_off[i] + (int64_t)kt * kBK);
-    }
+    for (int i = 0; i < C::A_LD; ++i) load_to_lds_addr(a_src[i] + (int64_t)kt * kBK, sA + (wave + C::NWAVE * i) * 1024);
 #pragma unroll
-    for (int i = 0; i < C::B_CH; ++i)
-      rb[i] = *reinterpret_cast<const u32x4*>(a.w + b_off[i] + (int64_t)kt * kBK);
+    for (int i = 0; i < C::B_LD; ++i)
+      load_to_lds(b_base + (int64_t)kt * kBK * 2, b_off[i], sB + (wave + C::NWAVE * i) * 1024);
   };
-  auto swrite = [&](int st) {
-    bf16_t* sA = sbase + st * C::STAGE;
-    bf16_t* sB = sA + C::BM * kLdsStride;
-#pragma unroll
-    for (int i = 0; i < C::A_CH; ++i) {
-      const int chunk = tid + i * C::NTHR;
-      *reinterpret_cast<u32x4*>(sA + (chunk >> 3) * kLdsStride + (chunk & 7) * 8) = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < C::B_CH; ++i) {
-      const int chunk = tid + i * C::NTHR;
-      *reinterpret_cast<u32x4*>(sB + (chunk >> 3) * kLdsStride + (chunk & 7) * 8) = rb[i];
-    }
-  };
+
+  // fragment addresses inside a stage: row (32-row tile base + l32), chunk 2*ks + hf in slot
+  // (2*ks + hf) ^ ((l32 / 2) % 8); the address of step ks is base ^ (32 * ks)
+  const int swz = (l32 >> 1) & 7;
+  const int fb0 = l32 * 128 + ((hf ^ (swz & 1)) * 16) + ((swz & 6) * 16);
+  const int a_frag = wm * 32 * TM * 128 + fb0;
+  const int b_frag = C::BM * kBK * 2 + wn * 32 * TN * 128 + fb0;
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -222,33 +222,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
     for (int j = 0; j < TN; ++j) acc[i][j] = floatx16{0};
 
   const int nk = a.d_model / kBK;
-  gload(0);
-  swrite(0);
-  __syncthreads();
+  issue(0, 0);
+  if (nk > 1) issue(1, 1);
   for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) gload(kt + 1);
-    const bf16_t* sA = sbase + (kt & 1) * C::STAGE;
-    const bf16_t* sB = sA + C::BM * kLdsStride;
-    const bf16_t* pa = sA + (wm * 32 * TM + (lane & 31)) * kLdsStride + 8 * (lane >> 5);
-    const bf16_t* pb = sB + (wn * 32 * TN + (lane & 31)) * kLdsStride + 8 * (lane >> 5);
+    // every wave has at most two stages of its own loads in flight; wait for the older one
+    if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::A_LD + C::B_LD) : "memory");
+    else __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();                       // stage kt%3 is complete; stage (kt+2)%3 is free again
+    if (kt + 2 < nk) issue(kt + 2, (kt + 2) % kStages);
+    const unsigned char* stage = smem + (size_t)(kt % kStages) * C::STAGE;
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
       bf16x8 af[TM], bfr[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pa + i * 32 * kLdsStride + ks * 16));
+        af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(stage + ((a_frag + i * 32 * 128) ^ (32 * ks))));
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pb + j * 32 * kLdsStride + ks * 16));
+        bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(stage + ((b_frag + j * 32 * 128) ^ (32 * ks))));
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) swrite((kt + 1) & 1);
-    __syncthreads();
   }
+  __syncthreads();                         // all fragment reads done before the epilogue reuses the LDS
 
   // epilogue: one slab of 32*TM rows at a time goes through LDS as fp32, then every thread
   // rotates 8 pairs (or copies 16 values) and stores two 16-byte vectors.
@@ -289,6 +288,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
       const float* row = sC + r * kCStride;
 #pragma unroll
       for (int p = 0; p < 8; ++p) { f[p] = row[e0 + p]; f[8 + p] = row[e1 + p]; }
+      if (a.gather) {                                  // an index outside x produces a zero row
+        const int64_t idx = a.gather[m];
+        if (idx < 0 || idx >= a.x_rows) {
+#pragma unroll
+          for (int p = 0; p < 16; ++p) f[p] = 0.f;
+        }
+      }
       if (rotate) {
         const float2* my = a.cs + m * half + i0;
 #pragma unroll
