@@ -231,20 +231,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
     __syncthreads();                       // stage kt%3 is complete; stage (kt+2)%3 is free again
     if (kt + 2 < nk) issue(kt + 2, (kt + 2) % kStages);
     const unsigned char* stage = smem + (size_t)(kt % kStages) * C::STAGE;
+    // fragments of step ks+1 are requested before the MFMAs of step ks are issued
+    u32x4 af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[0][i] = *reinterpret_cast<const u32x4*>(stage + (a_frag + i * 32 * 128));
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[0][j] = *reinterpret_cast<const u32x4*>(stage + (b_frag + j * 32 * 128));
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
-      bf16x8 af[TM], bfr[TN];
+      if (ks + 1 < kBK / 16) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(stage + ((a_frag + i * 32 * 128) ^ (32 * ks))));
+        for (int i = 0; i < TM; ++i)
+          af[(ks + 1) & 1][i] = *reinterpret_cast<const u32x4*>(stage + ((a_frag + i * 32 * 128) ^ (32 * (ks + 1))));
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(stage + ((b_frag + j * 32 * 128) ^ (32 * ks))));
+        for (int j = 0; j < TN; ++j)
+          bfr[(ks + 1) & 1][j] = *reinterpret_cast<const u32x4*>(stage + ((b_frag + j * 32 * 128) ^ (32 * (ks + 1))));
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[ks & 1][i]),
+                                                               __builtin_bit_cast(bf16x8, bfr[ks & 1][j]), acc[i][j], 0, 0, 0);
     }
   }
   __syncthreads();                         // all fragment reads done before the epilogue reuses the LDS
