@@ -149,3 +149,61 @@ def test_repeat_layer_is_bit_stable():
     torch.cuda.synchronize()
     for key in a:
         assert torch.equal(a[key].view(torch.uint8), b[key].view(torch.uint8)), key
+
+
+# ------------------------------------------------------------------ full-size configurations
+
+def test_config2_full_size_bench_configuration():
+    """The configuration bench.py times (8192 tokens, 16 ragged chunks, ratio 0.15), whole layer,
+    every output element against the oracle."""
+    wl = inputs.make_config(2, orc.PlantOps())
+    assert wl.requests[0].T == 8192 and wl.requests[0].R == 80
+    inputs.assert_bf16_headroom(wl)
+    check_layer(wl, 0.15)
+
+
+def test_config3_full_size_sampled_rows():
+    """70B-shaped layer, 32768 tokens: streaming, scoring and selection in full; projection and
+    attention against the oracle on sampled rows (the oracle computes those one by one)."""
+    wl = inputs.make_config(3, orc.PlantOps())
+    sh, req = wl.shape, wl.requests[0]
+    H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    qz = quantizer(sh.dtype)
+    say("  cfg3: upload + GPU layer")
+    L = pipeline.upload(wl, DEV)
+    out = pipeline.fuse_layer(L)
+    torch.cuda.synchronize()
+    say("  cfg3: oracle rerope / score / select")
+    kf, vf = orc.rerope([c.k for c in req.chunks], [c.v for c in req.chunks], req.dst_pos0, sh.rope_base)
+    kf, vf = qz(kf), qz(vf)
+    s_ref = orc.score(req.q_probe, kf)
+    n = orc.select_count(req.T, wl.ratio)
+    assert n == 4916 == L.total_sel
+    g = to_np(out["score"])
+    assert np.all(np.abs(g - s_ref) <= SCORE_REL * s_ref + 1e-12)
+    n_diff = assert_indices_match(out["sel_idx"].cpu().numpy(), s_ref, n, "cfg3")
+    idx = orc.select(s_ref, n)
+    if n_diff:
+        say(f"  {n_diff} indices inside the threshold band differ; re-running steps 4-6 on the oracle's set")
+        t = torch.from_numpy(idx.astype(np.int32)).to(DEV)
+        L.sel_idx[:n] = t; L.sel_row[:n] = t; L.sel_pos[:n] = t
+        pipeline.step_rerope(L); pipeline.step_qkv(L); pipeline.step_scatter(L); pipeline.step_attn(L)
+        torch.cuda.synchronize()
+    say("  cfg3: oracle K/V of all selected rows, Q and attention of sampled rows")
+    w = wl.w_qkv.astype(np.float64)
+    x_sel = req.x_ctx[idx].astype(np.float64)
+    y_kv = x_sel @ w[H * D:].T                                    # K heads then V heads
+    k_new = qz(orc.rope_at(y_kv[:, :Hkv * D].reshape(n, Hkv, D), idx, sh.rope_base))
+    v_new = qz(y_kv[:, Hkv * D:].reshape(n, Hkv, D))
+    kp, vp = orc.scatter(kf, vf, k_new, v_new, idx)
+    assert_close(to_np(out["k_fused"]), kp, sh.dtype, "patched K")
+    assert_close(to_np(out["v_fused"]), vp, sh.dtype, "patched V")
+    rows = np.sort(np.random.default_rng(3).choice(n, size=48, replace=False))
+    rows[0], rows[-1] = 0, n - 1
+    q_s, _, _ = orc.recompute_qkv(req.x_ctx[idx[rows]], wl.w_qkv, idx[rows], H, Hkv, D, sh.rope_base)
+    q_s = qz(q_s)
+    assert_close(to_np(out["q_sel"])[rows], q_s, sh.dtype, "Q rows")
+    o_ref, lse_ref = orc.recompute_attn(q_s, idx[rows], kp, vp)
+    err = assert_close(to_np(out["o_sel"])[rows], o_ref, sh.dtype, "O rows")
+    assert max_abs(to_np(out["lse"])[rows], lse_ref) < 5e-2
+    say(f"  cfg3: sampled O max abs err {err:.4f}")
