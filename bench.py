@@ -34,6 +34,8 @@ def parse_args():
     p.add_argument("--copies", type=int, default=6, help="independent buffer sets cycled through")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-sample-rows", type=int, default=256)
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     return p.parse_args()
 
 
@@ -135,6 +137,14 @@ def main():
     workload = f"cfg{args.config}: {len(req.chunks)} chunks, T={req.T}, R={req.R}, ratio={args.ratio}, " \
                f"N={layers[0].total_sel}, d_model={shape.d_model}, H={shape.n_q_heads}/{shape.n_kv_heads}, " \
                f"d={shape.head_dim}"
+
+    if args.calibrate_copy:          # 256 MiB read + 256 MiB written by one streaming kernel (negation)
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.neg(src, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     names = [n for n, _ in pipeline.STEPS]
     for i in range(args.warmup):
