@@ -132,6 +132,7 @@ struct QkvArgs {
   const float2* cs;
   int64_t x_rows, M;
   int d_model, H, Hkv, D;
+  int m_tiles, n_tiles;
   bf16_t* q;
   bf16_t* k;
   bf16_t* v;
@@ -162,8 +163,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int hf = lane >> 5, l32 = lane & 31;
-  const int64_t m0 = (int64_t)blockIdx.x * C::BM;
-  const int col0 = blockIdx.y * kBN;
+  // consecutive workgroup ids land on different XCDs: all row tiles of a column tile share an XCD, so
+  // the weight tile is fetched into one L2 only
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int m_tile = slot % a.m_tiles, n_tile = (slot / a.m_tiles) * 8 + xcd;
+  if (n_tile >= a.n_tiles) return;
+  const int64_t m0 = (int64_t)m_tile * C::BM;
+  const int col0 = n_tile * kBN;
 
   // which output does this column tile belong to
   const int q_cols = a.H * a.D, kv_cols = a.Hkv * a.D;
@@ -334,12 +340,16 @@ size_t cs_bytes(const qcf_layer_desc& L, int64_t M) {
 }
 
 template <int TM, int TN, int WGM, int WGN>
-qcf_status run_mfma(const qcf_layer_desc& L, const QkvArgs& a, hipStream_t st) {
+qcf_status run_mfma(const qcf_layer_desc& L, const QkvArgs& a_in, hipStream_t st) {
   using C = Tile<TM, TN, WGM, WGN>;
-  const int64_t mt = (a.M + C::BM - 1) / C::BM;
+  const int64_t mt = (a_in.M + C::BM - 1) / C::BM;
   const int nt = (L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim / kBN;
-  if (mt > 0x7fffffff || nt > 65535) return fail(QCF_ERR_UNSUPPORTED, "qkv: grid too large");
-  const dim3 grid((unsigned)mt, (unsigned)nt), block(C::NTHR);
+  const int64_t n_wg = mt * ((nt + 7) / 8) * 8;
+  if (mt > 0x7fffffff || n_wg > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "qkv: grid too large");
+  const dim3 grid((unsigned)n_wg), block(C::NTHR);
+  QkvArgs a = a_in;
+  a.m_tiles = (int)mt;
+  a.n_tiles = nt;
   static bool attr_done = false;
   if (!attr_done) {
     QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&qkv_mfma_kernel<TM, TN, WGM, WGN, 0>),
@@ -388,6 +398,7 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     a.x_rows = x_rows;
     a.M = M;
     a.d_model = L.d_model; a.H = H; a.Hkv = Hkv; a.D = D;
+    a.m_tiles = 0; a.n_tiles = 0;
     a.q = static_cast<bf16_t*>(q); a.k = static_cast<bf16_t*>(k); a.v = static_cast<bf16_t*>(v);
     // 256-row tiles when they still give every compute unit a workgroup, else 128-row tiles
     const int64_t tiles256 = ((M + 255) / 256) * (Ntot / kBN);
