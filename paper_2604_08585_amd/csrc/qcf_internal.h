@@ -132,6 +132,33 @@ __device__ __forceinline__ void load_to_lds_addr(const void* gptr, void* lds) {
                : "memory");
 }
 
+// The same two forms without the compiler-level memory fence: ordinary LDS accesses may be scheduled
+// across them (for loops that interleave these loads with fragment reads of another stage and order
+// everything with their own waits and barriers).
+// Form 1.
+__device__ __forceinline__ void load_to_lds_nf(const void* base, uint32_t lane_off, void* lds) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((int)lds_offset_of(lds));
+  const uint64_t b = (uint64_t)(uintptr_t)base;
+  // the builtin returns a signed int: widen through uint32_t, or a low half >= 2^31 would smear ones
+  // over the high half of the address
+  const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
+                      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
+               : "v"(lane_off), "s"(sb), "s"(lds_addr)
+               :);
+}
+// Form 2.
+__device__ __forceinline__ void load_to_lds_addr_nf(const void* gptr, void* lds) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((int)lds_offset_of(lds));
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
+               : "v"(gptr), "s"(lds_addr)
+               :);
+}
+
 // ---- launchers (one per translation unit) --------------------------------------
 // Each returns QCF_OK or an error after enqueueing on `st`; arguments were validated
 // by the entry points in api.hip.

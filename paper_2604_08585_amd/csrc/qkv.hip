@@ -214,6 +214,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
       load_to_lds(b_base + (int64_t)kt * kBK * 2, b_off[i], sB + (wave + C::NWAVE * i) * 1024);
   };
 
+  // the same loads split in four parts (part p issues every 4th instruction), so that they can be spread
+  // between the MFMAs of a k-tile
+  auto issue_part = [&](int kt, int st, int part) {
+    unsigned char* sA = smem + (size_t)st * C::STAGE;
+    unsigned char* sB = sA + C::BM * kBK * 2;
+#pragma unroll
+    for (int i = 0; i < C::A_LD; ++i)
+      if ((i & 3) == part) load_to_lds_addr_nf(a_src[i] + (int64_t)kt * kBK, sA + (wave + C::NWAVE * i) * 1024);
+#pragma unroll
+    for (int i = 0; i < C::B_LD; ++i)
+      if ((i & 3) == part) load_to_lds_nf(b_base + (int64_t)kt * kBK * 2, b_off[i], sB + (wave + C::NWAVE * i) * 1024);
+  };
+
   // fragment addresses inside a stage: row (32-row tile base + l32), chunk 2*ks + hf in slot
   // (2*ks + hf) ^ ((l32 / 2) % 8); the address of step ks is base ^ (32 * ks)
   const int swz = (l32 >> 1) & 7;
@@ -235,7 +248,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
     if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::A_LD + C::B_LD) : "memory");
     else __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();                       // stage kt%3 is complete; stage (kt+2)%3 is free again
-    if (kt + 2 < nk) issue(kt + 2, (kt + 2) % kStages);
+    const bool more = kt + 2 < nk;
+    const int st_next = (kt + 2) % kStages;
     const unsigned char* stage = smem + (size_t)(kt % kStages) * C::STAGE;
     // fragments of step ks+1 are requested before the MFMAs of step ks are issued
     u32x4 af[2][TM], bfr[2][TN];
@@ -253,6 +267,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
         for (int j = 0; j < TN; ++j)
           bfr[(ks + 1) & 1][j] = *reinterpret_cast<const u32x4*>(stage + ((b_frag + j * 32 * 128) ^ (32 * (ks + 1))));
       }
+      if (more) issue_part(kt + 2, st_next, ks);       // a quarter of the next-but-one stage per k-step
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
