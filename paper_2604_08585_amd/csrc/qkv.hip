@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void qkv_rope_split_generic(const float* __res
 
 constexpr int kBK = 64;                  // contraction elements per LDS stage (rows of 128 bytes)
 constexpr int kBN = 128;                 // output columns per workgroup (whole heads)
-constexpr int kCStride = kBN + 4;        // floats per row of the epilogue slab
+constexpr int kCStride = kBN + 8;        // floats per row of the epilogue tile (rows 4 apart: 32 banks apart)
 constexpr int kStages = 3;               // ring of LDS stages filled by asynchronous loads
 
 struct QkvArgs {
@@ -147,7 +147,7 @@ struct Tile {
   static constexpr int B_LD = kBN / 8 / NWAVE;
   static constexpr int STAGE = (BM + kBN) * kBK * 2;      // bytes per stage
   static constexpr size_t LDS_MAIN = (size_t)kStages * STAGE;
-  static constexpr size_t LDS_EPI = (size_t)32 * TM * kCStride * 4;
+  static constexpr size_t LDS_EPI = (size_t)BM * kCStride * 4;
   static constexpr size_t LDS = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
   static_assert(32 * TN * WGN == kBN, "a workgroup covers 128 output columns");
   static_assert((BM / 8) % NWAVE == 0 && (kBN / 8) % NWAVE == 0, "load split");
@@ -267,82 +267,104 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
         for (int j = 0; j < TN; ++j)
           bfr[(ks + 1) & 1][j] = *reinterpret_cast<const u32x4*>(stage + ((b_frag + j * 32 * 128) ^ (32 * (ks + 1))));
       }
-      if (more) issue_part(kt + 2, st_next, ks);       // a quarter of the next-but-one stage per k-step
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i) {
+        // a quarter of the next-but-one stage per k-step, requested while the matrix unit is busy
+        if (i == TM / 2 && more) issue_part(kt + 2, st_next, ks);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[ks & 1][i]),
                                                                __builtin_bit_cast(bf16x8, bfr[ks & 1][j]), acc[i][j], 0, 0, 0);
+      }
     }
   }
   __syncthreads();                         // all fragment reads done before the epilogue reuses the LDS
 
-  // epilogue: one slab of 32*TM rows at a time goes through LDS as fp32, then every thread
-  // rotates 8 pairs (or copies 16 values) and stores two 16-byte vectors.
+  // epilogue: every wave drops its accumulators into LDS as fp32 (the whole BM x 128 tile fits in the
+  // ring's space), then each thread takes the same 16 columns (8 rotary pairs) of NT rows: it first
+  // requests the gather indices and rotary factors of all its rows, then rotates and stores two 16-byte
+  // vectors per row.
   float* sC = reinterpret_cast<float*>(smem);
-  constexpr int SLAB = 32 * TM;
-  const int half = a.D / 2;
-  for (int slab = 0; slab < WGM; ++slab) {
-    if (wm == slab) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int r = i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            const int c = wn * 32 * TN + j * 32 + (lane & 31);
-            sC[r * kCStride + c] = acc[i][j][v];
-          }
-    }
-    __syncthreads();
-    for (int task = tid; task < SLAB * 8; task += C::NTHR) {
-      const int r = task >> 3, tk = task & 7;
-      const int64_t m = m0 + slab * SLAB + r;
-      if (m >= a.M) continue;
-      int e0, e1, i0;
-      if (STYLE == 0) {
-        const int per_head = a.D / 16;               // tasks per head
-        const int hd = tk / per_head;
-        i0 = (tk - hd * per_head) * 8;
-        e0 = hd * a.D + i0;
-        e1 = e0 + half;
-      } else {
-        e0 = tk * 16;
-        e1 = e0 + 8;
-        i0 = (e0 % a.D) / 2;
+      for (int v = 0; v < 16; ++v) {
+        const int r = (wm * TM + i) * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+        const int c = (wn * TN + j) * 32 + l32;
+        sC[r * kCStride + c] = acc[i][j][v];
       }
-      float f[16], o[16];
-      const float* row = sC + r * kCStride;
+  __syncthreads();
+
+  constexpr int NT = C::BM * 8 / C::NTHR;              // rows per thread
+  constexpr int RSTEP = C::NTHR / 8;                   // row distance between a thread's tasks
+  const int half = a.D / 2;
+  const int tk = tid & 7, r0 = tid >> 3;
+  int e0, e1, i0;
+  if (STYLE == 0) {
+    const int per_head = a.D / 16;                     // tasks per head
+    const int hd = tk / per_head;
+    i0 = (tk - hd * per_head) * 8;
+    e0 = hd * a.D + i0;
+    e1 = e0 + half;
+  } else {
+    e0 = tk * 16;
+    e1 = e0 + 8;
+    i0 = (e0 % a.D) / 2;
+  }
+  bool zero[NT];
+  u32x4 w4[NT][4];                                     // 8 (cos, sin) pairs per row
 #pragma unroll
-      for (int p = 0; p < 8; ++p) { f[p] = row[e0 + p]; f[8 + p] = row[e1 + p]; }
+  for (int t = 0; t < NT; ++t) {
+    const int64_t m = m0 + r0 + t * RSTEP;
+    zero[t] = false;
+    if (m < a.M) {
       if (a.gather) {                                  // an index outside x produces a zero row
         const int64_t idx = a.gather[m];
-        if (idx < 0 || idx >= a.x_rows) {
-#pragma unroll
-          for (int p = 0; p < 16; ++p) f[p] = 0.f;
-        }
+        zero[t] = idx < 0 || idx >= a.x_rows;
       }
       if (rotate) {
-        const float2* my = a.cs + m * half + i0;
+        const u32x4* my = reinterpret_cast<const u32x4*>(a.cs + m * half + i0);
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          const float2 w = my[p];
-          const int ia = (STYLE == 0) ? p : 2 * p;
-          const int ib = (STYLE == 0) ? p + 8 : 2 * p + 1;
-          o[ia] = f[ia] * w.x - f[ib] * w.y;
-          o[ib] = f[ib] * w.x + f[ia] * w.y;
-        }
-      } else {
-#pragma unroll
-        for (int p = 0; p < 16; ++p) o[p] = f[p];
+        for (int p = 0; p < 4; ++p) w4[t][p] = my[p];
       }
-      bf16_t* dst = out + m * out_cols + out_col0;
-      *reinterpret_cast<u32x4*>(dst + e0) = Vec16<bf16_t>::pack(o);
-      *reinterpret_cast<u32x4*>(dst + e1) = Vec16<bf16_t>::pack(o + 8);
     }
-    __syncthreads();
+  }
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int r = r0 + t * RSTEP;
+    const int64_t m = m0 + r;
+    if (m >= a.M) continue;
+    float f[16], o[16];
+    const float* row = sC + r * kCStride;
+    {
+      const u32x4 c0 = *reinterpret_cast<const u32x4*>(row + e0), c1 = *reinterpret_cast<const u32x4*>(row + e0 + 4);
+      const u32x4 c2 = *reinterpret_cast<const u32x4*>(row + e1), c3 = *reinterpret_cast<const u32x4*>(row + e1 + 4);
+      Vec16<float>::unpack(c0, f); Vec16<float>::unpack(c1, f + 4);
+      Vec16<float>::unpack(c2, f + 8); Vec16<float>::unpack(c3, f + 12);
+    }
+    if (zero[t]) {
+#pragma unroll
+      for (int p = 0; p < 16; ++p) f[p] = 0.f;
+    }
+    if (rotate) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const float wx = __uint_as_float(w4[t][p >> 1][(p & 1) * 2]);
+        const float wy = __uint_as_float(w4[t][p >> 1][(p & 1) * 2 + 1]);
+        const int ia = (STYLE == 0) ? p : 2 * p;
+        const int ib = (STYLE == 0) ? p + 8 : 2 * p + 1;
+        o[ia] = f[ia] * wx - f[ib] * wy;
+        o[ib] = f[ib] * wx + f[ia] * wy;
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < 16; ++p) o[p] = f[p];
+    }
+    bf16_t* dst = out + m * out_cols + out_col0;
+    *reinterpret_cast<u32x4*>(dst + e0) = Vec16<bf16_t>::pack(o);
+    *reinterpret_cast<u32x4*>(dst + e1) = Vec16<bf16_t>::pack(o + 8);
   }
 }
 
