@@ -153,6 +153,117 @@ struct Tile {
   static_assert((BM / 8) % NWAVE == 0 && (kBN / 8) % NWAVE == 0, "load split");
 };
 
+// Where a 128-column tile of the fused projection goes.
+struct OutTile {
+  bf16_t* out;
+  int out_cols, out_col0;
+  bool rotate;
+};
+__device__ __forceinline__ OutTile out_tile_of(const QkvArgs& a, int col0) {
+  const int q_cols = a.H * a.D, kv_cols = a.Hkv * a.D;
+  OutTile o;
+  o.rotate = true;
+  if (col0 < q_cols) { o.out = a.q; o.out_cols = q_cols; o.out_col0 = col0; }
+  else if (col0 < q_cols + kv_cols) { o.out = a.k; o.out_cols = kv_cols; o.out_col0 = col0 - q_cols; }
+  else { o.out = a.v; o.out_cols = kv_cols; o.out_col0 = col0 - q_cols - kv_cols; o.rotate = false; }
+  return o;
+}
+
+// Epilogue, first half: a wave drops its accumulators (32*TM rows from row_base, 32*TN columns from
+// col_base) into the fp32 tile in LDS.
+template <int TM, int TN>
+__device__ __forceinline__ void acc_to_lds(float* sC, const floatx16 (&acc)[TM][TN], int row_base, int col_base,
+                                           int lane) {
+  const int hf = lane >> 5, l32 = lane & 31;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = row_base + i * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+        const int c = col_base + j * 32 + l32;
+        sC[r * kCStride + c] = acc[i][j][v];
+      }
+}
+
+// Epilogue, second half (after a barrier): each thread takes the same 16 columns (8 rotary pairs) of
+// BM*8/NTHR rows.  It first requests the gather indices and rotary factors of all its rows, then rotates
+// and stores two 16-byte vectors per row.
+template <int BM, int NTHR, int STYLE>
+__device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, int64_t m0, const OutTile& ot, int tid) {
+  constexpr int NT = BM * 8 / NTHR;                    // rows per thread
+  constexpr int RSTEP = NTHR / 8;                      // row distance between a thread's tasks
+  static_assert(BM * 8 % NTHR == 0, "rows per thread");
+  const int half = a.D / 2;
+  const int tk = tid & 7, r0 = tid >> 3;
+  int e0, e1, i0;
+  if (STYLE == 0) {
+    const int per_head = a.D / 16;                     // tasks per head
+    const int hd = tk / per_head;
+    i0 = (tk - hd * per_head) * 8;
+    e0 = hd * a.D + i0;
+    e1 = e0 + half;
+  } else {
+    e0 = tk * 16;
+    e1 = e0 + 8;
+    i0 = (e0 % a.D) / 2;
+  }
+  bool zero[NT];
+  u32x4 w4[NT][4];                                     // 8 (cos, sin) pairs per row
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int64_t m = m0 + r0 + t * RSTEP;
+    zero[t] = false;
+    if (m < a.M) {
+      if (a.gather) {                                  // an index outside x produces a zero row
+        const int64_t idx = a.gather[m];
+        zero[t] = idx < 0 || idx >= a.x_rows;
+      }
+      if (ot.rotate) {
+        const u32x4* my = reinterpret_cast<const u32x4*>(a.cs + m * half + i0);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) w4[t][p] = my[p];
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int r = r0 + t * RSTEP;
+    const int64_t m = m0 + r;
+    if (m >= a.M) continue;
+    float f[16], o[16];
+    const float* row = sC + r * kCStride;
+    {
+      const u32x4 c0 = *reinterpret_cast<const u32x4*>(row + e0), c1 = *reinterpret_cast<const u32x4*>(row + e0 + 4);
+      const u32x4 c2 = *reinterpret_cast<const u32x4*>(row + e1), c3 = *reinterpret_cast<const u32x4*>(row + e1 + 4);
+      Vec16<float>::unpack(c0, f); Vec16<float>::unpack(c1, f + 4);
+      Vec16<float>::unpack(c2, f + 8); Vec16<float>::unpack(c3, f + 12);
+    }
+    if (zero[t]) {
+#pragma unroll
+      for (int p = 0; p < 16; ++p) f[p] = 0.f;
+    }
+    if (ot.rotate) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const float wx = __uint_as_float(w4[t][p >> 1][(p & 1) * 2]);
+        const float wy = __uint_as_float(w4[t][p >> 1][(p & 1) * 2 + 1]);
+        const int ia = (STYLE == 0) ? p : 2 * p;
+        const int ib = (STYLE == 0) ? p + 8 : 2 * p + 1;
+        o[ia] = f[ia] * wx - f[ib] * wy;
+        o[ib] = f[ib] * wx + f[ia] * wy;
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < 16; ++p) o[p] = f[p];
+    }
+    bf16_t* dst = ot.out + m * ot.out_cols + ot.out_col0;
+    *reinterpret_cast<u32x4*>(dst + e0) = Vec16<bf16_t>::pack(o);
+    *reinterpret_cast<u32x4*>(dst + e1) = Vec16<bf16_t>::pack(o + 8);
+  }
+}
+
 // Staged tiles have rows of 128 bytes (8 chunks of 16 bytes) without padding; chunk c of row r sits in
 // slot c ^ ((r / 2) % 8), so the 16-byte fragment reads of 16 consecutive rows touch 16 different bank
 // groups.  One load instruction of a wave fills 8 rows (1 KB): lane L fills slot L%8 of row L/8.
@@ -171,15 +282,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
   const int64_t m0 = (int64_t)m_tile * C::BM;
   const int col0 = n_tile * kBN;
 
-  // which output does this column tile belong to
-  const int q_cols = a.H * a.D, kv_cols = a.Hkv * a.D;
-  bf16_t* out;
-  int out_cols, out_col0;
-  bool rotate = true;
-  if (col0 < q_cols) { out = a.q; out_cols = q_cols; out_col0 = col0; }
-  else if (col0 < q_cols + kv_cols) { out = a.k; out_cols = kv_cols; out_col0 = col0 - q_cols; }
-  else { out = a.v; out_cols = kv_cols; out_col0 = col0 - q_cols - kv_cols; rotate = false; }
-  if (!out) return;
+  const OutTile ot = out_tile_of(a, col0);
+  if (!ot.out) return;
 
   // load instruction i of this wave covers tile rows 8*(wave + NWAVE*i) .. +7
   const int ld_r = lane >> 3;                                    // row inside the 8-row group
@@ -280,92 +384,153 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
   }
   __syncthreads();                         // all fragment reads done before the epilogue reuses the LDS
 
-  // epilogue: every wave drops its accumulators into LDS as fp32 (the whole BM x 128 tile fits in the
-  // ring's space), then each thread takes the same 16 columns (8 rotary pairs) of NT rows: it first
-  // requests the gather indices and rotary factors of all its rows, then rotates and stores two 16-byte
-  // vectors per row.
+  // epilogue: the whole BM x 128 tile goes through LDS as fp32 (it fits in the ring's space)
   float* sC = reinterpret_cast<float*>(smem);
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = (wm * TM + i) * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-        const int c = (wn * TN + j) * 32 + l32;
-        sC[r * kCStride + c] = acc[i][j][v];
-      }
+  acc_to_lds<TM, TN>(sC, acc, wm * 32 * TM, wn * 32 * TN, lane);
   __syncthreads();
+  store_tile<C::BM, C::NTHR, STYLE>(a, sC, m0, ot, tid);
+}
 
-  constexpr int NT = C::BM * 8 / C::NTHR;              // rows per thread
-  constexpr int RSTEP = C::NTHR / 8;                   // row distance between a thread's tasks
-  const int half = a.D / 2;
-  const int tk = tid & 7, r0 = tid >> 3;
-  int e0, e1, i0;
-  if (STYLE == 0) {
-    const int per_head = a.D / 16;                     // tasks per head
-    const int hd = tk / per_head;
-    i0 = (tk - hd * per_head) * 8;
-    e0 = hd * a.D + i0;
-    e1 = e0 + half;
-  } else {
-    e0 = tk * 16;
-    e1 = e0 + 8;
-    i0 = (e0 % a.D) / 2;
-  }
-  bool zero[NT];
-  u32x4 w4[NT][4];                                     // 8 (cos, sin) pairs per row
+// ---- specialised variant for 256-row tiles ---------------------------------------------------------
+// Four compute waves (one per SIMD, 64 x 128 outputs each) issue only fragment reads and MFMAs; four more
+// waves only issue the asynchronous global-to-LDS loads.  A wave that issues such a load can stall on the
+// memory pipeline's queue, and a stalled wave issues no MFMAs either: with the two roles in different
+// waves the matrix unit keeps running meanwhile.
+//
+// Synchronisation, one barrier per k-tile (barrier number kt + 1 is crossed while tile kt is computed):
+//   compute wave: steps 0..2 of tile kt, wait for its last fragment reads of stage kt%3, barrier,
+//                 request the first fragments of tile kt+1, step 3 of tile kt;
+//   load wave:    after barrier kt it requests tile kt+2 into stage (kt+2)%3 == (kt-1)%3 (free: every
+//                 compute wave finished reading tile kt-1 before barrier kt), waits until its loads of
+//                 tile kt+1 have landed, barrier.
+struct WsTile {
+  static constexpr int TM = 2, TN = 4, NC = 4, NL = 4;            // compute waves stacked along M
+  static constexpr int BM = 32 * TM * NC;                         // 256
+  static constexpr int NTHR = 64 * (NC + NL);
+  static constexpr int A_LD = BM / 8 / NL;                        // 1 KB load instructions per load wave and stage
+  static constexpr int B_LD = kBN / 8 / NL;
+  static constexpr int STAGE = (BM + kBN) * kBK * 2;
+  static constexpr size_t LDS_MAIN = (size_t)kStages * STAGE;
+  static constexpr size_t LDS_EPI = (size_t)BM * kCStride * 4;
+  static constexpr size_t LDS = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+  static_assert(32 * TN == kBN, "a compute wave covers the 128 output columns");
+};
+
+template <int STYLE>
+__global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
+  using C = WsTile;
+  constexpr int TM = C::TM, TN = C::TN;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int hf = lane >> 5, l32 = lane & 31;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;        // same workgroup order as above
+  const int m_tile = slot % a.m_tiles, n_tile = (slot / a.m_tiles) * 8 + xcd;
+  if (n_tile >= a.n_tiles) return;
+  const int64_t m0 = (int64_t)m_tile * C::BM;
+  const int col0 = n_tile * kBN;
+  const OutTile ot = out_tile_of(a, col0);
+  if (!ot.out) return;
+  const int nk = a.d_model / kBK;
+  float* sC = reinterpret_cast<float*>(smem);
+
+  if (wave >= C::NC) {
+    // ---------------- load wave lw: instruction i covers tile rows 8*(lw + NL*i) .. +7
+    const int lw = wave - C::NC;
+    const int ld_r = lane >> 3;
+    const bf16_t* a_src[C::A_LD];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int64_t m = m0 + r0 + t * RSTEP;
-    zero[t] = false;
-    if (m < a.M) {
-      if (a.gather) {                                  // an index outside x produces a zero row
-        const int64_t idx = a.gather[m];
-        zero[t] = idx < 0 || idx >= a.x_rows;
+    for (int i = 0; i < C::A_LD; ++i) {
+      const int row = 8 * (lw + C::NL * i) + ld_r;
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      const int64_t m = m0 + row;
+      int64_t idx = 0;                                           // rows past M read row 0; never stored
+      if (m < a.M) {
+        idx = a.gather ? (int64_t)a.gather[m] : m;
+        if (idx < 0 || idx >= a.x_rows) idx = 0;                 // stored as zeros in the epilogue
       }
-      if (rotate) {
-        const u32x4* my = reinterpret_cast<const u32x4*>(a.cs + m * half + i0);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) w4[t][p] = my[p];
-      }
+      a_src[i] = a.x + idx * a.d_model + chunk * 8;
     }
-  }
+    uint32_t b_off[C::B_LD];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int r = r0 + t * RSTEP;
-    const int64_t m = m0 + r;
-    if (m >= a.M) continue;
-    float f[16], o[16];
-    const float* row = sC + r * kCStride;
-    {
-      const u32x4 c0 = *reinterpret_cast<const u32x4*>(row + e0), c1 = *reinterpret_cast<const u32x4*>(row + e0 + 4);
-      const u32x4 c2 = *reinterpret_cast<const u32x4*>(row + e1), c3 = *reinterpret_cast<const u32x4*>(row + e1 + 4);
-      Vec16<float>::unpack(c0, f); Vec16<float>::unpack(c1, f + 4);
-      Vec16<float>::unpack(c2, f + 8); Vec16<float>::unpack(c3, f + 12);
+    for (int i = 0; i < C::B_LD; ++i) {
+      const int row = 8 * (lw + C::NL * i) + ld_r;
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      b_off[i] = (uint32_t)row * (uint32_t)a.d_model * 2u + (uint32_t)chunk * 16u;
     }
-    if (zero[t]) {
+    const char* b_base = reinterpret_cast<const char*>(a.w + (int64_t)col0 * a.d_model);
+    auto issue = [&](int kt) {
+      unsigned char* sA = smem + (size_t)(kt % kStages) * C::STAGE;
+      unsigned char* sB = sA + C::BM * kBK * 2;
 #pragma unroll
-      for (int p = 0; p < 16; ++p) f[p] = 0.f;
-    }
-    if (rotate) {
+      for (int i = 0; i < C::B_LD; ++i)
+        load_to_lds(b_base + (int64_t)kt * kBK * 2, b_off[i], sB + (lw + C::NL * i) * 1024);
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const float wx = __uint_as_float(w4[t][p >> 1][(p & 1) * 2]);
-        const float wy = __uint_as_float(w4[t][p >> 1][(p & 1) * 2 + 1]);
-        const int ia = (STYLE == 0) ? p : 2 * p;
-        const int ib = (STYLE == 0) ? p + 8 : 2 * p + 1;
-        o[ia] = f[ia] * wx - f[ib] * wy;
-        o[ib] = f[ib] * wx + f[ia] * wy;
-      }
+      for (int i = 0; i < C::A_LD; ++i) load_to_lds_addr(a_src[i] + (int64_t)kt * kBK, sA + (lw + C::NL * i) * 1024);
+    };
+    issue(0);
+    if (nk > 1) {
+      issue(1);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::A_LD + C::B_LD) : "memory");
     } else {
-#pragma unroll
-      for (int p = 0; p < 16; ++p) o[p] = f[p];
+      __builtin_amdgcn_s_waitcnt(0);
     }
-    bf16_t* dst = out + m * out_cols + out_col0;
-    *reinterpret_cast<u32x4*>(dst + e0) = Vec16<bf16_t>::pack(o);
-    *reinterpret_cast<u32x4*>(dst + e1) = Vec16<bf16_t>::pack(o + 8);
+    __syncthreads();                                             // barrier 0: tile 0 has landed
+    for (int kt = 0; kt < nk; ++kt) {
+      if (kt + 2 < nk) {
+        issue(kt + 2);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::A_LD + C::B_LD) : "memory");
+      } else {
+        __builtin_amdgcn_s_waitcnt(0);
+      }
+      __syncthreads();                                           // barrier kt + 1: tile kt + 1 has landed
+    }
+    __syncthreads();                                             // the accumulators are in LDS
+  } else {
+    // ---------------- compute wave: rows 64*wave .. +63 of the tile, all 128 columns
+    const int swz = (l32 >> 1) & 7;
+    const int fb0 = l32 * 128 + ((hf ^ (swz & 1)) * 16) + ((swz & 6) * 16);
+    const int a_frag = wave * 32 * TM * 128 + fb0;
+    const int b_frag = C::BM * kBK * 2 + fb0;
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = floatx16{0};
+    u32x4 af[2][TM], bfr[2][TN];
+    auto fetch = [&](const unsigned char* stage, int ks, int buf) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[buf][i] = *reinterpret_cast<const u32x4*>(stage + ((a_frag + i * 32 * 128) ^ (32 * ks)));
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bfr[buf][j] = *reinterpret_cast<const u32x4*>(stage + ((b_frag + j * 32 * 128) ^ (32 * ks)));
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[buf][i]),
+                                                               __builtin_bit_cast(bf16x8, bfr[buf][j]), acc[i][j], 0, 0, 0);
+    };
+    __syncthreads();                                             // barrier 0
+    fetch(smem, 0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      const unsigned char* stage = smem + (size_t)(kt % kStages) * C::STAGE;
+#pragma unroll
+      for (int ks = 0; ks < 3; ++ks) {
+        fetch(stage, ks + 1, (ks + 1) & 1);
+        mfmas(ks & 1);
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // the last fragments of this stage are in registers
+      __syncthreads();                                           // barrier kt + 1
+      if (kt + 1 < nk) fetch(smem + (size_t)((kt + 1) % kStages) * C::STAGE, 0, 0);
+      mfmas(1);
+    }
+    acc_to_lds<TM, TN>(sC, acc, wave * 32 * TM, 0, lane);
+    __syncthreads();
   }
+  store_tile<C::BM, C::NTHR, STYLE>(a, sC, m0, ot, tid);
 }
 
 bool use_mfma(const qcf_layer_desc& L) {
@@ -397,6 +562,29 @@ qcf_status run_mfma(const qcf_layer_desc& L, const QkvArgs& a_in, hipStream_t st
   }
   if (L.rope_style == 0) qkv_mfma_kernel<TM, TN, WGM, WGN, 0><<<grid, block, C::LDS, st>>>(a);
   else qkv_mfma_kernel<TM, TN, WGM, WGN, 1><<<grid, block, C::LDS, st>>>(a);
+  return check_launch("qkv gemm");
+}
+
+qcf_status run_ws(const qcf_layer_desc& L, const QkvArgs& a_in, hipStream_t st) {
+  using C = WsTile;
+  const int64_t mt = (a_in.M + C::BM - 1) / C::BM;
+  const int nt = (L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim / kBN;
+  const int64_t n_wg = mt * ((nt + 7) / 8) * 8;
+  if (mt > 0x7fffffff || n_wg > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "qkv: grid too large");
+  const dim3 grid((unsigned)n_wg), block(C::NTHR);
+  QkvArgs a = a_in;
+  a.m_tiles = (int)mt;
+  a.n_tiles = nt;
+  static bool attr_done = false;
+  if (!attr_done) {
+    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&qkv_ws_kernel<0>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS), "qkv attr"));
+    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&qkv_ws_kernel<1>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS), "qkv attr"));
+    attr_done = true;
+  }
+  if (L.rope_style == 0) qkv_ws_kernel<0><<<grid, block, C::LDS, st>>>(a);
+  else qkv_ws_kernel<1><<<grid, block, C::LDS, st>>>(a);
   return check_launch("qkv gemm");
 }
 
@@ -439,7 +627,7 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     a.q = static_cast<bf16_t*>(q); a.k = static_cast<bf16_t*>(k); a.v = static_cast<bf16_t*>(v);
     // 256-row tiles when they still give every compute unit a workgroup, else 128-row tiles
     const int64_t tiles256 = ((M + 255) / 256) * (Ntot / kBN);
-    if (tiles256 >= 200) return run_mfma<2, 4, 4, 1>(L, a, st);
+    if (tiles256 >= 200) return run_ws(L, a, st);
     return run_mfma<2, 2, 2, 2>(L, a, st);
   }
   float* y = reinterpret_cast<float*>(static_cast<char*>(ws) + cs_bytes(L, M));
