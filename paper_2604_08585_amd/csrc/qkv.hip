@@ -437,7 +437,7 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
     // ---------------- load wave lw: instruction i covers tile rows 8*(lw + NL*i) .. +7
     const int lw = wave - C::NC;
     const int ld_r = lane >> 3;
-    const bf16_t* a_src[C::A_LD];
+    uint32_t a_off[C::A_LD];                                     // byte offset from x (x is below 4 GiB here)
 #pragma unroll
     for (int i = 0; i < C::A_LD; ++i) {
       const int row = 8 * (lw + C::NL * i) + ld_r;
@@ -448,8 +448,9 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
         idx = a.gather ? (int64_t)a.gather[m] : m;
         if (idx < 0 || idx >= a.x_rows) idx = 0;                 // stored as zeros in the epilogue
       }
-      a_src[i] = a.x + idx * a.d_model + chunk * 8;
+      a_off[i] = (uint32_t)idx * (uint32_t)a.d_model * 2u + (uint32_t)chunk * 16u;
     }
+    const char* a_base = reinterpret_cast<const char*>(a.x);
     uint32_t b_off[C::B_LD];
 #pragma unroll
     for (int i = 0; i < C::B_LD; ++i) {
@@ -465,7 +466,8 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
       for (int i = 0; i < C::B_LD; ++i)
         load_to_lds(b_base + (int64_t)kt * kBK * 2, b_off[i], sB + (lw + C::NL * i) * 1024);
 #pragma unroll
-      for (int i = 0; i < C::A_LD; ++i) load_to_lds_addr(a_src[i] + (int64_t)kt * kBK, sA + (lw + C::NL * i) * 1024);
+      for (int i = 0; i < C::A_LD; ++i)
+        load_to_lds(a_base + (int64_t)kt * kBK * 2, a_off[i], sA + (lw + C::NL * i) * 1024);
     };
     issue(0);
     if (nk > 1) {
@@ -487,6 +489,7 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
     __syncthreads();                                             // the accumulators are in LDS
   } else {
     // ---------------- compute wave: rows 64*wave .. +63 of the tile, all 128 columns
+    __builtin_amdgcn_s_setprio(2);                               // its instructions go first when both roles are ready
     const int swz = (l32 >> 1) & 7;
     const int fb0 = l32 * 128 + ((hf ^ (swz & 1)) * 16) + ((swz & 6) * 16);
     const int a_frag = wave * 32 * TM * 128 + fb0;
@@ -513,6 +516,16 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[buf][i]),
                                                                __builtin_bit_cast(bf16x8, bfr[buf][j]), acc[i][j], 0, 0, 0);
     };
+    // issue order of one k-step: every fragment read sits behind an MFMA, so that the matrix unit is
+    // already busy while the read is issued
+    auto interleave = [&]() {
+#pragma unroll
+      for (int q = 0; q < TM + TN; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // one LDS read
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+    };
     __syncthreads();                                             // barrier 0
     fetch(smem, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
@@ -521,12 +534,16 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
       for (int ks = 0; ks < 3; ++ks) {
         fetch(stage, ks + 1, (ks + 1) & 1);
         mfmas(ks & 1);
+        interleave();
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // the last fragments of this stage are in registers
       __syncthreads();                                           // barrier kt + 1
-      if (kt + 1 < nk) fetch(smem + (size_t)((kt + 1) % kStages) * C::STAGE, 0, 0);
+      // (after the last tile this re-reads the current stage; the values are not used)
+      fetch(smem + (size_t)((kt + 1 < nk ? kt + 1 : kt) % kStages) * C::STAGE, 0, 0);
       mfmas(1);
+      interleave();
     }
+    __builtin_amdgcn_s_setprio(0);
     acc_to_lds<TM, TN>(sC, acc, wave * 32 * TM, 0, lane);
     __syncthreads();
   }
@@ -627,7 +644,9 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     a.q = static_cast<bf16_t*>(q); a.k = static_cast<bf16_t*>(k); a.v = static_cast<bf16_t*>(v);
     // 256-row tiles when they still give every compute unit a workgroup, else 128-row tiles
     const int64_t tiles256 = ((M + 255) / 256) * (Ntot / kBN);
-    if (tiles256 >= 200) return run_ws(L, a, st);
+    // (the specialised kernel addresses x with 32-bit byte offsets)
+    if (tiles256 >= 200 && (uint64_t)x_rows * (uint64_t)L.d_model * 2u < (1ull << 32)) return run_ws(L, a, st);
+    if (tiles256 >= 200) return run_mfma<2, 4, 4, 1>(L, a, st);
     return run_mfma<2, 2, 2, 2>(L, a, st);
   }
   float* y = reinterpret_cast<float*>(static_cast<char*>(ws) + cs_bytes(L, M));
