@@ -8,7 +8,10 @@
 // exchange between the two lane halves; the probabilities, still in registers, are already
 // the B operand of O^T += V^T P^T.  V tiles are transposed on their way into LDS.  Key tiles
 // wholly above a wave's highest position are skipped, tiles wholly below its lowest run
-// unmasked, only the straddling tiles compare positions.
+// unmasked, only the straddling tiles compare positions.  When the launch has too few row blocks
+// to balance the causal triangle over the compute units, a row block's keys are cut into segments
+// that run as separate workgroups; each writes a normalised partial output and its log-sum-exp,
+// and a second kernel merges them (the usual softmax merge, exact up to rounding).
 //
 // Generic path (f32, or other shapes): one workgroup per (row, head), online softmax over
 // 256-token tiles.
@@ -44,6 +47,11 @@ struct AttnArgs {
   void* o;
   float* lse;
   int n_row_blocks;      // upper bound on row blocks over all requests (MFMA path)
+  int seg_tiles;         // key tiles per work unit; a row block with more tiles is split over units
+  int n_seg_max;         // units per row block the grid provides
+  bf16_t* part_o;        // [unit][128 rows][128] normalised partial outputs of split row blocks
+  float* part_lse;       // [unit][128 rows] log2-domain log-sum-exp of each partial (-inf: no visible key)
+  int32_t* units;        // units[0] = number of work units, then (row block << 8 | segment), longest first
 };
 
 // ------------------------------------------------------------------ generic path
@@ -142,8 +150,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
 
   // consecutive workgroup ids land on different XCDs: give each XCD its own KV heads so that a
   // head's keys and values stay in one L2; later row blocks (longer key ranges) are scheduled first
+  // Unsplit launches take the row blocks from the last (longest key range) to the first.  Split launches
+  // read the unit list attn_plan_kernel sorted by length; segments are counted from the top of a block's
+  // key range, so a block's remainder segment is the one at the start of the context.
   const int g = (int)(blockIdx.x % a.Hkv);
-  int wg = a.n_row_blocks - 1 - (int)(blockIdx.x / a.Hkv);
+  const int unit = (int)(blockIdx.x / a.Hkv);
+  int seg = 0, blk = a.n_row_blocks - 1 - unit;
+  if (a.units) {
+    if (unit >= a.units[0]) return;
+    const int code = a.units[1 + unit];
+    blk = code >> 8;
+    seg = code & 255;
+  }
+  int wg = blk;
   int b = 0;
   int64_t s0 = 0, s1 = 0;
   for (; b < a.B; ++b) {
@@ -176,6 +195,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   __syncthreads();
   const int wg_vis_max = max(max(s_vis_max[0], s_vis_max[1]), max(s_vis_max[2], s_vis_max[3]));
   const int n_tiles = (wg_vis_max + kBKV - 1) / kBKV;
+  const bool split = n_tiles > a.seg_tiles;
+  if (seg > 0 && seg * a.seg_tiles >= n_tiles) return;      // this block has fewer segments
+  const int t_end = n_tiles - seg * a.seg_tiles;
+  const int t_begin = max(0, t_end - a.seg_tiles);
   if (n_tiles == 0) {                 // nothing visible to any row of the block
     if (row_ok) {
       bf16_t* op = static_cast<bf16_t*>(a.o) + (srow * a.H + head) * 128 + 64 * hf;
@@ -215,7 +238,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     aload(vg, ld_voff, ld_vchunk, t, sbase + st * kStage + kKTile + (4 * wave) * 128);
   };
   auto aload2 = [&](int t, int st) { aload_k(t, st); aload_v(t, st); };
-  aload2(0, 0);
+  aload2(t_begin, 0);
 
   // stationary query fragments: qf[ks] = row r, elements 16*ks + 8*hf .. +7
   bf16x8 qf[8];
@@ -327,21 +350,38 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     }
   };
 
-  for (int t = 0; t < n_tiles; t += 2) {
+  for (int t = t_begin; t < t_end; t += 2) {
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();                                  // tile t has landed; stage 1 is free again
-    if (t + 1 < n_tiles) aload2(t + 1, 1);
+    if (t + 1 < t_end) aload2(t + 1, 1);
     if (t * kBKV < wave_vis_max) process(smem, t * kBKV);
-    if (t + 1 >= n_tiles) break;
+    if (t + 1 >= t_end) break;
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (t + 2 < n_tiles) aload2(t + 2, 0);
+    if (t + 2 < t_end) aload2(t + 2, 0);
     if ((t + 1) * kBKV < wave_vis_max) process(smem + (size_t)kStage * 2, (t + 1) * kBKV);
   }
 
   // epilogue: output register v of tile dt is element 32*dt + 16*hf + v of this lane's row
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  if (split) {                        // partial result of one key segment; merged by attn_merge_kernel
+    const int64_t slot = ((int64_t)blk * a.Hkv + g) * a.n_seg_max + seg;
+    bf16_t* op = a.part_o + (slot * kRowsPerWg + r) * 128 + 16 * hf;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+      for (int h8 = 0; h8 < 2; ++h8) {
+        const u32x4 pk = mk4(cvt_pk_bf16(oacc[dt][8 * h8 + 0] * inv, oacc[dt][8 * h8 + 1] * inv),
+                             cvt_pk_bf16(oacc[dt][8 * h8 + 2] * inv, oacc[dt][8 * h8 + 3] * inv),
+                             cvt_pk_bf16(oacc[dt][8 * h8 + 4] * inv, oacc[dt][8 * h8 + 5] * inv),
+                             cvt_pk_bf16(oacc[dt][8 * h8 + 6] * inv, oacc[dt][8 * h8 + 7] * inv));
+        *reinterpret_cast<u32x4*>(op + 32 * dt + 8 * h8) = pk;
+      }
+    }
+    if (hf == 0) a.part_lse[slot * kRowsPerWg + r] = l_tot > 0.f ? m_run + log2f(l_tot) : -INFINITY;
+    return;
+  }
   if (row_ok) {
     bf16_t* op = static_cast<bf16_t*>(a.o) + (srow * a.H + head) * 128 + 16 * hf;
 #pragma unroll
@@ -360,6 +400,161 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   }
 }
 
+// Work list of a split launch: one entry per (row block, key segment) that has tiles, bucket-sorted by
+// length (longest first) so that the short remainders fill the tail of the schedule.  The order inside a
+// bucket depends on the race for the slots; results do not, because every unit's output location is given
+// by its (row block, segment).
+constexpr int kPlanBins = 64;
+constexpr int kPlanMaxBlocks = 4096;        // row blocks a split launch may have (LDS table of the plan kernel)
+__global__ __launch_bounds__(1024) void attn_plan_kernel(AttnArgs a) {
+  __shared__ int s_vis[kPlanMaxBlocks];     // largest visible length of each row block
+  __shared__ int s_cnt[kPlanBins + 1];
+  __shared__ int s_off[kPlanBins + 1];
+  const int tid = threadIdx.x;
+  const int BR = kRowsPerWg / a.G;
+  for (int i = tid; i < a.n_row_blocks; i += 1024) s_vis[i] = 0;
+  for (int i = tid; i <= kPlanBins; i += 1024) s_cnt[i] = 0;
+  __syncthreads();
+  // every selected row raises the visible length of its block
+  for (int64_t sr = tid; sr < a.total_sel; sr += 1024) {
+    int blk0 = 0, b = 0;
+    int64_t s0 = 0, s1 = 0;
+    for (; b < a.B; ++b) {
+      s0 = min(max(a.sel_off[b], (int64_t)0), a.total_sel);
+      s1 = min(max(a.sel_off[b + 1], s0), a.total_sel);
+      if (sr >= s0 && sr < s1) break;
+      blk0 += (int)((s1 - s0 + BR - 1) / BR);
+    }
+    if (b >= a.B) continue;
+    const int64_t c0 = min(max(a.ctx_off[b], (int64_t)0), a.total_ctx);
+    const int64_t c1 = min(max(a.ctx_off[b + 1], c0), a.total_ctx);
+    const int64_t p0 = a.ctx_pos0 ? a.ctx_pos0[b] : 0;
+    const int vis = (int)min(c1 - c0, max((int64_t)0, (int64_t)a.sel_pos[sr] - p0 + 1));
+    atomicMax(&s_vis[blk0 + (int)((sr - s0) / BR)], vis);
+  }
+  __syncthreads();
+  // pass 0 counts the units of every length bucket, pass 1 places them
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int blk = tid; blk < a.n_row_blocks; blk += 1024) {
+      const int n_tiles = (s_vis[blk] + kBKV - 1) / kBKV;
+      const int n_seg = max(1, (n_tiles + a.seg_tiles - 1) / a.seg_tiles);   // a block without tiles still writes zeros
+      for (int sg = 0; sg < n_seg; ++sg) {
+        const int len = min(a.seg_tiles, n_tiles - sg * a.seg_tiles);
+        const int bin = kPlanBins - (int)((int64_t)max(len, 0) * kPlanBins / a.seg_tiles);   // 0: whole segments
+        if (pass == 0) atomicAdd(&s_cnt[bin], 1);
+        else a.units[1 + atomicAdd(&s_off[bin], 1)] = (blk << 8) | sg;
+      }
+    }
+    __syncthreads();
+    if (pass == 0) {
+      if (tid == 0) {
+        int run = 0;
+        for (int i = 0; i <= kPlanBins; ++i) { s_off[i] = run; run += s_cnt[i]; }
+        a.units[0] = run;
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// Merge of the partial results of split row blocks: kMergeWgs workgroups per (row block, KV head), one
+// thread per 8 output elements.  out = sum_s w_s O_s with w_s = 2^(lse_s - lse), lse = log2 sum_s 2^lse_s.
+constexpr int kMergeWgs = kRowsPerWg * 16 / 256;
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
+  __shared__ int s_vis[kRowsPerWg];
+  const int tid = threadIdx.x;
+  const int BR = kRowsPerWg / a.G;
+  const int part = (int)(blockIdx.x % kMergeWgs);
+  const int bh = (int)(blockIdx.x / kMergeWgs);
+  const int g = bh % a.Hkv;
+  const int blk = bh / a.Hkv;
+  int wg = blk, b = 0;
+  int64_t s0 = 0, s1 = 0;
+  for (; b < a.B; ++b) {
+    s0 = min(max(a.sel_off[b], (int64_t)0), a.total_sel);
+    s1 = min(max(a.sel_off[b + 1], s0), a.total_sel);
+    const int nb = (int)((s1 - s0 + BR - 1) / BR);
+    if (wg < nb) break;
+    wg -= nb;
+  }
+  if (b >= a.B) return;
+  const int64_t c0 = min(max(a.ctx_off[b], (int64_t)0), a.total_ctx);
+  const int64_t c1 = min(max(a.ctx_off[b + 1], c0), a.total_ctx);
+  const int T = (int)(c1 - c0);
+  const int64_t p0 = a.ctx_pos0 ? a.ctx_pos0[b] : 0;
+  if (tid < BR) {
+    const int64_t sr = s0 + (int64_t)wg * BR + tid;
+    s_vis[tid] = sr < s1 ? (int)min((int64_t)T, max((int64_t)0, (int64_t)a.sel_pos[sr] - p0 + 1)) : 0;
+  }
+  __syncthreads();
+  int vis_max = 0;
+  for (int i = 0; i < BR; ++i) vis_max = max(vis_max, s_vis[i]);
+  const int n_tiles = (vis_max + kBKV - 1) / kBKV;
+  if (n_tiles <= a.seg_tiles) return;               // not split: the main kernel wrote the result
+  const int n_seg = (n_tiles + a.seg_tiles - 1) / a.seg_tiles;
+  const int r = part * 16 + (tid >> 4), ch = tid & 15;          // row of the block, 8-element chunk
+  const int64_t srow = s0 + (int64_t)wg * BR + r / a.G;
+  if (srow >= s1) return;
+  const int head = g * a.G + r % a.G;
+  // unit (blk, g, seg) wrote slot ((blk * Hkv + g) * n_seg_max + seg)
+  const int64_t slot0 = ((int64_t)blk * a.Hkv + g) * a.n_seg_max;
+  const float* pl = a.part_lse + slot0 * kRowsPerWg + r;
+  const bf16_t* po = a.part_o + (slot0 * kRowsPerWg + r) * 128 + 8 * ch;
+  float mx = -INFINITY;
+#pragma unroll 4
+  for (int sg = 0; sg < n_seg; ++sg) mx = fmaxf(mx, pl[(int64_t)sg * kRowsPerWg]);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float wsum = 0.f;
+  if (mx > -INFINITY) {
+#pragma unroll 4
+    for (int sg = 0; sg < n_seg; ++sg) {
+      const float w = __builtin_amdgcn_exp2f(pl[(int64_t)sg * kRowsPerWg] - mx);
+      float f[8];
+      Vec16<bf16_t>::unpack(*reinterpret_cast<const u32x4*>(po + (int64_t)sg * kRowsPerWg * 128), f);
+      wsum += w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += w * f[e];
+    }
+  }
+  const float inv = wsum > 0.f ? 1.f / wsum : 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] *= inv;
+  *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(a.o) + (srow * a.H + head) * 128 + 8 * ch) = Vec16<bf16_t>::pack(acc);
+  if (a.lse && ch == 0) a.lse[srow * a.H + head] = wsum > 0.f ? (mx + log2f(wsum)) * kLn2 : -INFINITY;
+}
+
+// Key tiles per work unit.  With enough row blocks the causal triangle balances by itself and blocks
+// stay whole; otherwise segments are sized so that the units outnumber the resident workgroups.
+struct Split { int seg_tiles, n_seg_max; };
+Split choose_split(int64_t n_blocks, int64_t total_ctx) {
+  static int slots = 0;
+  if (slots == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    slots = 2 * cus;                                  // two workgroups are resident per compute unit
+  }
+  const int64_t n_t = std::max<int64_t>(1, (total_ctx + kBKV - 1) / kBKV);
+  const int64_t per_slot = n_blocks * ((n_t + 1) / 2) / slots;     // average causal work per resident workgroup
+  int64_t seg = 8;
+  while (seg * 2 <= per_slot) seg *= 2;
+  while ((n_t + seg - 1) / seg > 256) seg *= 2;       // a unit's segment number is kept in 8 bits
+  if (n_blocks > kPlanMaxBlocks) seg = n_t;            // (never the case when splitting pays: see per_slot)
+  if (seg >= n_t) return Split{(int)std::min<int64_t>(n_t, 0x3fffffff), 1};
+  return Split{(int)seg, (int)((n_t + seg - 1) / seg)};
+}
+
+size_t part_o_bytes(int64_t n_blocks, int n_seg_max) {
+  return align_up((size_t)n_blocks * n_seg_max * kRowsPerWg * 128 * sizeof(bf16_t), 256);
+}
+size_t part_lse_bytes(int64_t n_blocks, int n_seg_max) {
+  return align_up((size_t)n_blocks * n_seg_max * kRowsPerWg * sizeof(float), 256);
+}
+size_t units_bytes(int64_t n_row_blocks, int n_seg_max) {
+  return align_up((size_t)(n_row_blocks * n_seg_max + 1) * sizeof(int32_t), 256);
+}
+
 bool use_mfma(const qcf_layer_desc& L) {
   const int G = L.n_q_heads / L.n_kv_heads;
   return L.dtype == QCF_DTYPE_BF16 && L.head_dim == 128 && G <= kRowsPerWg && kRowsPerWg % G == 0;
@@ -367,12 +562,20 @@ bool use_mfma(const qcf_layer_desc& L) {
 
 }  // namespace
 
-size_t attn_workspace(const qcf_layer_desc&, int32_t, int64_t, int64_t) { return 0; }
+size_t attn_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_sel, int64_t total_ctx) {
+  if (!use_mfma(L) || total_sel <= 0 || total_ctx <= 0) return 0;
+  const int BR = kRowsPerWg / (L.n_q_heads / L.n_kv_heads);
+  const int64_t n_blocks = ((total_sel + BR - 1) / BR + B) * L.n_kv_heads;
+  const Split sp = choose_split(n_blocks, total_ctx);
+  if (sp.n_seg_max <= 1) return 0;
+  return part_o_bytes(n_blocks, sp.n_seg_max) + part_lse_bytes(n_blocks, sp.n_seg_max) +
+         units_bytes(n_blocks / L.n_kv_heads, sp.n_seg_max);
+}
 
 qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const int32_t* sel_pos,
                        const int64_t* sel_off, int64_t total_sel, const void* k, const void* v,
                        const int64_t* ctx_off, int64_t total_ctx, const int32_t* ctx_pos0, void* o,
-                       float* lse, void*, hipStream_t st) {
+                       float* lse, void* ws, hipStream_t st) {
   AttnArgs a;
   a.q = q; a.k = k; a.v = v;
   a.sel_pos = sel_pos; a.sel_off = sel_off; a.ctx_off = ctx_off; a.ctx_pos0 = ctx_pos0;
@@ -380,19 +583,40 @@ qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const 
   a.B = B; a.H = L.n_q_heads; a.Hkv = L.n_kv_heads; a.G = L.n_q_heads / L.n_kv_heads; a.D = L.head_dim;
   a.o = o; a.lse = lse;
   a.n_row_blocks = 0;
+  a.seg_tiles = 0x3fffffff; a.n_seg_max = 1; a.part_o = nullptr; a.part_lse = nullptr; a.units = nullptr;
   if (use_mfma(L)) {
     const int BR = kRowsPerWg / a.G;
     const int64_t nb = (total_sel + BR - 1) / BR + B;
-    if (nb * a.Hkv > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "attn: grid too large");
+    const Split sp = choose_split(nb * a.Hkv, total_ctx);
+    if (nb * a.Hkv * std::max(sp.n_seg_max, kMergeWgs) > 0x7fffffff)
+      return fail(QCF_ERR_UNSUPPORTED, "attn: grid too large");
     a.n_row_blocks = (int)nb;
+    a.seg_tiles = sp.seg_tiles;
+    a.n_seg_max = sp.n_seg_max;
+    if (sp.n_seg_max > 1) {
+      a.part_o = static_cast<bf16_t*>(ws);
+      char* w = static_cast<char*>(ws);
+      a.part_lse = reinterpret_cast<float*>(w + part_o_bytes(nb * a.Hkv, sp.n_seg_max));
+      a.units = reinterpret_cast<int32_t*>(w + part_o_bytes(nb * a.Hkv, sp.n_seg_max) +
+                                           part_lse_bytes(nb * a.Hkv, sp.n_seg_max));
+    }
     static bool attr_done = false;
     if (!attr_done) {
       QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds), "attn attr"));
       attr_done = true;
     }
-    attn_mfma_kernel<<<dim3((unsigned)(nb * a.Hkv)), dim3(256), kAttnLds, st>>>(a);
-    return check_launch("attn");
+    if (sp.n_seg_max > 1) {
+      attn_plan_kernel<<<dim3(1), dim3(1024), 0, st>>>(a);
+      QCF_TRY_LAUNCH("attn plan");
+    }
+    attn_mfma_kernel<<<dim3((unsigned)(nb * a.Hkv * sp.n_seg_max)), dim3(256), kAttnLds, st>>>(a);
+    QCF_TRY_LAUNCH("attn");
+    if (sp.n_seg_max > 1) {
+      attn_merge_kernel<<<dim3((unsigned)(nb * a.Hkv * kMergeWgs)), dim3(256), 0, st>>>(a);
+      return check_launch("attn merge");
+    }
+    return QCF_OK;
   }
   if (total_sel * a.H > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "attn: grid too large");
   const dim3 grid((unsigned)(total_sel * a.H)), block(256);
