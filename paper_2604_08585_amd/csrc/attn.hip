@@ -130,9 +130,12 @@ constexpr int kRowsPerWg = 128;             // (selected row, head-in-group) pai
 
 // LDS transposing read: within each group of 16 lanes, lane i receives element i%4 of the four
 // 8-byte rows addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4 of the group.
-__device__ __forceinline__ shortx4 lds_read_tr(const unsigned char* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (shortx4 __attribute__((address_space(3)))*)(const_cast<unsigned char*>(p)));
+__device__ __forceinline__ shortx4 lds_read_tr(uint32_t lds_addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(uintptr_t)lds_addr);
+}
+// 16-byte LDS read at a byte address (a register plus a compile-time constant becomes the offset field)
+__device__ __forceinline__ u32x4 lds_read16(uint32_t lds_addr) {
+  return *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)lds_addr;
 }
 
 // Tile layouts in LDS (rows of 256 bytes = 16 chunks of 16 bytes, no padding):
@@ -142,11 +145,12 @@ __device__ __forceinline__ shortx4 lds_read_tr(const unsigned char* p) {
 //           8 consecutive rows x 64 bytes touch every bank exactly twice.
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  bf16_t* sbase = reinterpret_cast<bf16_t*>(smem);
   __shared__ int s_vis_max[4];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: keeps tile addresses in scalar registers
   const int hf = lane >> 5, l32 = lane & 31;
   const int BR = kRowsPerWg / a.G;           // selected rows per workgroup
+  const uint32_t lds0 = lds_offset_of(smem);
 
   // consecutive workgroup ids land on different XCDs: give each XCD its own KV heads so that a
   // head's keys and values stay in one L2; later row blocks (longer key ranges) are scheduled first
@@ -220,22 +224,22 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   const uint32_t ld_vchunk = (uint32_t)(((lane & 15) ^ (4 * (ld_row & 3))) * 16);
   const uint32_t ld_koff = (uint32_t)ld_row * row_bytes + ld_kchunk;
   const uint32_t ld_voff = (uint32_t)ld_row * row_bytes + ld_vchunk;
-  auto aload = [&](const bf16_t* src, uint32_t off0, uint32_t chunk, int t, bf16_t* dst) {
+  auto aload = [&](const bf16_t* src, uint32_t off0, uint32_t chunk, int t, uint32_t dst) {
     const char* base = reinterpret_cast<const char*>(src) + (int64_t)t * kBKV * row_bytes;
     if (t * kBKV + kBKV <= T) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) load_to_lds(base + (size_t)(16 * i) * row_bytes, off0, dst + (16 * i) * 128);
+      for (int i = 0; i < 4; ++i) load_to_lds_at(base + (size_t)(16 * i) * row_bytes, off0, dst + (16 * i) * 256);
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = min(16 * i + ld_row, T - 1 - t * kBKV);
-        load_to_lds(base, (uint32_t)row * row_bytes + chunk, dst + (16 * i) * 128);
+        load_to_lds_at(base, (uint32_t)row * row_bytes + chunk, dst + (16 * i) * 256);
       }
     }
   };
-  auto aload_k = [&](int t, int st) { aload(kg, ld_koff, ld_kchunk, t, sbase + st * kStage + (4 * wave) * 128); };
+  auto aload_k = [&](int t, int st) { aload(kg, ld_koff, ld_kchunk, t, lds0 + st * kStage * 2 + (4 * wave) * 256); };
   auto aload_v = [&](int t, int st) {
-    aload(vg, ld_voff, ld_vchunk, t, sbase + st * kStage + kKTile + (4 * wave) * 128);
+    aload(vg, ld_voff, ld_vchunk, t, lds0 + st * kStage * 2 + kKTile * 2 + (4 * wave) * 256);
   };
   auto aload2 = [&](int t, int st) { aload_k(t, st); aload_v(t, st); };
   aload2(t_begin, 0);
@@ -253,21 +257,21 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   }
 
   // per-lane byte offsets of the fragment reads inside a stage
-  int kofs[8];     // key fragment ks: token row l32 (+32), chunk 2*ks + hf
+  uint32_t kofs[8];     // key fragment ks: token row l32 (+32), chunk 2*ks + hf
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) kofs[ks] = l32 * 256 + (((2 * ks + hf) ^ (l32 & 15)) * 16);
+  for (int ks = 0; ks < 8; ++ks) kofs[ks] = lds0 + l32 * 256 + (((2 * ks + hf) ^ (l32 & 15)) * 16);
   // values: the lane addresses the 8-byte piece (token 4*hf + (lane%16)/4, elements d0 .. d0+3) where
   // block q = 4*((lane/16)%2) + lane%4 of a 32-element slice starts at d0 = 16*(q%2) + 4*(q/2); after the
   // transposing read lane (row i = lane%32) holds four consecutive tokens of element
   // 16*(i/4 % 2) + 4*(i/8) + i%4, which makes MFMA output row 8b + 4h + c element 16h + 4b + c
-  int vofs[4];     // value fragment of output tile dt
+  uint32_t vofs[4];     // value fragment of output tile dt
   {
     const int vq = 4 * ((lane >> 4) & 1) + (lane & 3);
     const int d0 = 16 * (vq & 1) + 4 * (vq >> 1);
     const int vrow = 4 * hf + ((lane & 15) >> 2);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
-      vofs[dt] = kKTile * 2 + vrow * 256 + (((4 * dt + d0 / 8) ^ (4 * (vrow & 3))) * 16) + (d0 & 4) * 2;
+      vofs[dt] = lds0 + kKTile * 2 + vrow * 256 + (((4 * dt + d0 / 8) ^ (4 * (vrow & 3))) * 16) + (d0 & 4) * 2;
   }
 
   floatx16 oacc[4];
@@ -277,17 +281,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   float l_run = 0.f;            // this lane's share of the running denominator
   const float k2 = kLog2e * 0.08838834764831845f;
 
-  auto process = [&](const unsigned char* stage, int kv0) {
+  auto process = [&](const uint32_t stage, int kv0) {        // stage: byte offset of the stage (a constant at each call)
     floatx16 sa = {0}, sb = {0};
     {
       u32x4 fa[2], fb[2];
-      fa[0] = *reinterpret_cast<const u32x4*>(stage + kofs[0]);
-      fb[0] = *reinterpret_cast<const u32x4*>(stage + kofs[0] + 32 * 256);
+      fa[0] = lds_read16(kofs[0] + stage);
+      fb[0] = lds_read16(kofs[0] + (stage + 32 * 256));
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         if (ks < 7) {
-          fa[(ks + 1) & 1] = *reinterpret_cast<const u32x4*>(stage + kofs[ks + 1]);
-          fb[(ks + 1) & 1] = *reinterpret_cast<const u32x4*>(stage + kofs[ks + 1] + 32 * 256);
+          fa[(ks + 1) & 1] = lds_read16(kofs[ks + 1] + stage);
+          fb[(ks + 1) & 1] = lds_read16(kofs[ks + 1] + (stage + 32 * 256));
         }
         sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[ks & 1]), qf[ks], sa, 0, 0, 0);
         sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[ks & 1]), qf[ks], sb, 0, 0, 0);
@@ -295,8 +299,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     }
     // first value fragments can travel while the softmax runs
     shortx4 vlo[2], vhi[2];
-    vlo[0] = lds_read_tr(stage + vofs[0]);
-    vhi[0] = lds_read_tr(stage + vofs[0] + 8 * 256);
+    vlo[0] = lds_read_tr(vofs[0] + stage);
+    vhi[0] = lds_read_tr(vofs[0] + (stage + 8 * 256));
     // register v of sa is token kv0 + 8*(v/4) + 4*hf + v%4 (sb: + 32) against this lane's row
     float p[32];
 #pragma unroll
@@ -342,8 +346,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       const int s = idx >> 2, dt = idx & 3;
       if (idx < 15) {
         const int s2 = (idx + 1) >> 2, dt2 = (idx + 1) & 3;
-        vlo[(idx + 1) & 1] = lds_read_tr(stage + vofs[dt2] + (16 * s2) * 256);
-        vhi[(idx + 1) & 1] = lds_read_tr(stage + vofs[dt2] + (16 * s2 + 8) * 256);
+        vlo[(idx + 1) & 1] = lds_read_tr(vofs[dt2] + (stage + (16 * s2) * 256));
+        vhi[(idx + 1) & 1] = lds_read_tr(vofs[dt2] + (stage + (16 * s2 + 8) * 256));
       }
       const shortx8 both = __builtin_shufflevector(vlo[idx & 1], vhi[idx & 1], 0, 1, 2, 3, 4, 5, 6, 7);
       oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[s], oacc[dt], 0, 0, 0);
@@ -354,12 +358,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();                                  // tile t has landed; stage 1 is free again
     if (t + 1 < t_end) aload2(t + 1, 1);
-    if (t * kBKV < wave_vis_max) process(smem, t * kBKV);
+    if (t * kBKV < wave_vis_max) process(0u, t * kBKV);
     if (t + 1 >= t_end) break;
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (t + 2 < t_end) aload2(t + 2, 0);
-    if ((t + 1) * kBKV < wave_vis_max) process(smem + (size_t)kStage * 2, (t + 1) * kBKV);
+    if ((t + 1) * kBKV < wave_vis_max) process((uint32_t)kStage * 2u, (t + 1) * kBKV);
   }
 
   // epilogue: output register v of tile dt is element 32*dt + 16*hf + v of this lane's row

@@ -122,6 +122,18 @@ __device__ __forceinline__ void load_to_lds(const void* base, uint32_t lane_off,
                : "v"(lane_off), "s"(sb), "s"(lds_addr)
                : "memory");
 }
+// Form 1 with the LDS destination given as a byte address (wave-uniform).
+__device__ __forceinline__ void load_to_lds_at(const void* base, uint32_t lane_off, uint32_t lds_addr_in) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((int)lds_addr_in);
+  const uint64_t b = (uint64_t)(uintptr_t)base;
+  const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
+                      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
+               : "v"(lane_off), "s"(sb), "s"(lds_addr)
+               : "memory");
+}
 // Form 2: a full 64-bit address per lane.
 __device__ __forceinline__ void load_to_lds_addr(const void* gptr, void* lds) {
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((int)lds_offset_of(lds));
