@@ -254,6 +254,35 @@ def test_qkv_large_tile_config_and_partial_outputs():
     _qkv_case(shape_bf16(), 70, 100, seed=23, outputs=(False, True, True))
 
 
+def test_qkv_activation_matrix_beyond_4_gib():
+    # rows are gathered from both sides of the 4 GiB line of x: byte offsets no longer fit 32 bits, so the
+    # launcher must take the tiling that addresses x with 64-bit pointers
+    sh = shape_bf16(d_model=256, H=32, Hkv=8, D=128)
+    rng = np.random.default_rng(24)
+    dt = inputs.torch_dtype(sh.dtype)
+    H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    line = (1 << 32) // (sh.d_model * 2)                 # first row that starts at or beyond 4 GiB
+    x_rows = line + 6000
+    M = 256 * 4 + 19
+    g = np.sort(np.concatenate([rng.choice(3000, size=M // 2, replace=False),
+                                line - 200 + rng.choice(6200, size=M - M // 2, replace=False)])).astype(np.int32)
+    say(f"qkv x beyond 4 GiB: x_rows={x_rows} M={M} rows past the line: {(g >= line).sum()}")
+    xg = rnd(rng, (M, sh.d_model), sh.dtype)
+    w = rnd(rng, (sh.qkv_rows, sh.d_model), sh.dtype, std=1 / math.sqrt(sh.d_model))
+    pos = np.sort(rng.integers(0, 40000, size=M)).astype(np.int32)
+    x_dev = torch.empty((x_rows, sh.d_model), dtype=dt, device=DEV)      # only the gathered rows are defined
+    x_dev[torch.from_numpy(g.astype(np.int64)).to(DEV)] = to_dev(xg, dt)
+    q = torch.full((M, H, D), 7.0, dtype=dt, device=DEV)
+    k = torch.full((M, Hkv, D), 7.0, dtype=dt, device=DEV)
+    v = torch.full((M, Hkv, D), 7.0, dtype=dt, device=DEV)
+    qb.qcf_recompute_qkv(qb.make_desc(sh), x_dev, x_rows, i32(g), M, to_dev(w, dt), i32(pos), q, k, v)
+    torch.cuda.synchronize()
+    del x_dev
+    rq, rk, rv = orc.recompute_qkv(xg, w, pos, H, Hkv, D, sh.rope_base, sh.rope_style)
+    for t, r, name in ((q, rq, "q"), (k, rk, "k"), (v, rv, "v")):
+        assert_close(to_np(t), r, sh.dtype, f"{name} (x beyond 4 GiB)")
+
+
 # ------------------------------------------------------------------ scatter
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
