@@ -203,6 +203,9 @@ def main():
         "config": {"workload": workload, "buffer_copies": len(layers)},
         "roofline": roofline,
         "kernels": kernels,
+        # token analysis runs once per request (critical layer only), reconstruction at every layer
+        "analysis_ms": round(per_call["score"] + per_call["select"], 5),
+        "reconstruction_ms": round(per_call["rerope"] + per_call["qkv"] + per_call["scatter"] + per_call["attn"], 5),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.ratio, args.cpu_sample_rows)
