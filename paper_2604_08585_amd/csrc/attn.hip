@@ -528,7 +528,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
 }
 
 // Key tiles per work unit.  With enough row blocks the causal triangle balances by itself and blocks
-// stay whole; otherwise segments are sized so that the units outnumber the resident workgroups.
+// stay whole; otherwise a segment is about the average causal work of a resident workgroup.
 struct Split { int seg_tiles, n_seg_max; };
 Split choose_split(int64_t n_blocks, int64_t total_ctx) {
   static int slots = 0;
@@ -541,8 +541,9 @@ Split choose_split(int64_t n_blocks, int64_t total_ctx) {
   }
   const int64_t n_t = std::max<int64_t>(1, (total_ctx + kBKV - 1) / kBKV);
   const int64_t per_slot = n_blocks * ((n_t + 1) / 2) / slots;     // average causal work per resident workgroup
-  int64_t seg = 8;
-  while (seg * 2 <= per_slot) seg *= 2;
+  // a little above that average (a multiple of 4 tiles): most resident workgroups then take one whole
+  // segment and the remainders fill the rest (measured best at recompute ratios 0.05, 0.15 and 0.30)
+  int64_t seg = std::max<int64_t>(8, (per_slot * 27 / 25 + 3) / 4 * 4);
   while ((n_t + seg - 1) / seg > 256) seg *= 2;       // a unit's segment number is kept in 8 bits
   if (n_blocks > kPlanMaxBlocks) seg = n_t;            // (never the case when splitting pays: see per_slot)
   if (seg >= n_t) return Split{(int)std::min<int64_t>(n_t, 0x3fffffff), 1};
