@@ -39,17 +39,18 @@ def parse_args():
     return p.parse_args()
 
 
-def algorithmic_work(L, sel_pos_host, shape):
+def algorithmic_work(L, sel_pos_host, shape, requests):
     """Bytes / flops the method itself must move / compute per call (no tile padding, only the
-    unmasked part of the causal attention)."""
+    unmasked part of the causal attention).  T, R, N are totals over the requests of the batch."""
     s = 2 if shape.dtype == "bf16" else 4
     T, R, N = L.total_ctx, L.total_probe, L.total_sel
     H, Hkv, D, dm = shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_model
     kv_row = Hkv * D * s
     vis = int(sum(int(p) + 1 for p in sel_pos_host))
+    score_flops = sum(2 * r.R * H * r.T * D for r in requests)      # every probe row against its own context
     return {
         "rerope": {"bytes": 4 * T * kv_row, "flops": 0},                              # K and V, read + write
-        "score": {"bytes": T * kv_row + R * H * D * s + 4 * T, "flops": 2 * R * H * T * D},
+        "score": {"bytes": T * kv_row + R * H * D * s + 4 * T, "flops": score_flops},
         "select": {"bytes": 4 * T + 4 * N, "flops": 0},
         "qkv": {"bytes": (N * dm + (H + 2 * Hkv) * D * dm + N * (H + 2 * Hkv) * D) * s,
                 "flops": 2 * N * dm * (H + 2 * Hkv) * D},
@@ -134,9 +135,12 @@ def main():
     layers = []
     for c in range(max(1, args.copies)):
         layers.append(pipeline.upload(wl, dev, ratio=args.ratio, shared_chunks={}))
-    workload = f"cfg{args.config}: {len(req.chunks)} chunks, T={req.T}, R={req.R}, ratio={args.ratio}, " \
-               f"N={layers[0].total_sel}, d_model={shape.d_model}, H={shape.n_q_heads}/{shape.n_kv_heads}, " \
-               f"d={shape.head_dim}"
+    n_req = len(wl.requests)
+    total_T = sum(r.T for r in wl.requests)
+    workload = f"cfg{args.config}: {n_req} request{'s' if n_req > 1 else ''}, " \
+               f"{sum(len(r.chunks) for r in wl.requests)} chunks, T={total_T}, R={sum(r.R for r in wl.requests)}, " \
+               f"ratio={args.ratio}, N={layers[0].total_sel}, d_model={shape.d_model}, " \
+               f"H={shape.n_q_heads}/{shape.n_kv_heads}, d={shape.head_dim}"
 
     if args.calibrate_copy:          # 256 MiB read + 256 MiB written by one streaming kernel (negation)
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
@@ -169,7 +173,7 @@ def main():
     per_call = {n: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]))
                 for j, n in enumerate(names)}
 
-    work = algorithmic_work(layers[0], sel_pos_host, shape)
+    work = algorithmic_work(layers[0], sel_pos_host, shape, wl.requests)
     kernels = {}
     for n in names:
         ms = per_call[n]
@@ -194,7 +198,7 @@ def main():
 
     out = {
         "metric": "fused-layer context tokens/sec + per-layer fusion latency (ms) at 8K ctx",
-        "value": round(req.T / (ms_per_step * 1e-3), 1),
+        "value": round(total_T / (ms_per_step * 1e-3), 1),
         "unit": "context tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
