@@ -151,27 +151,42 @@ def main():
         del src, dst
 
     names = [n for n, _ in pipeline.STEPS]
+
+    def run_with_events(n_steps, first, only=None):
+        """n_steps layers back to back; events on the launch stream (torch's current stream) bracket every
+        call, or only call `only`.  Returns (wall seconds, mean ms per bracketed call)."""
+        which = range(len(names)) if only is None else [names.index(only)]
+        ev = [{j: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for j in which}
+              for _ in range(n_steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_steps):
+            L = layers[(first + i) % len(layers)]
+            for j, (_, fn) in enumerate(pipeline.STEPS):
+                if j in ev[i]:
+                    ev[i][j][0].record()
+                fn(L)
+                if j in ev[i]:
+                    ev[i][j][1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall, {names[j]: float(np.mean([ev[i][j][0].elapsed_time(ev[i][j][1]) for i in range(n_steps)]))
+                      for j in which}
+
+    # untimed warmup; its last steps carry events around every call: they give the per-call table and
+    # name the dominant call
     for i in range(args.warmup):
         pipeline.enqueue_layer(layers[i % len(layers)])
     torch.cuda.synchronize()
     sel_pos_host = layers[0].sel_pos[:layers[0].total_sel].cpu().numpy()
+    _, per_call = run_with_events(max(10, min(50, args.steps)), args.warmup)
+    dominant = max(names, key=lambda n: per_call[n])
 
-    # timed region: exactly `steps` layers back to back; events bracket every call on the stream the
-    # kernels are launched on (torch's current stream)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        L = layers[i % len(layers)]
-        ev[i][0].record()
-        for j, (_, fn) in enumerate(pipeline.STEPS):
-            fn(L)
-            ev[i][j + 1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    # timed region: exactly `steps` layers back to back, events around the dominant call only (an event
+    # pair around each of the six calls costs several microseconds per layer at this scale)
+    wall, dom = run_with_events(args.steps, 0, only=dominant)
     ms_per_step = wall * 1e3 / args.steps
-    per_call = {n: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]))
-                for j, n in enumerate(names)}
+    per_call[dominant] = dom[dominant]
 
     work = algorithmic_work(layers[0], sel_pos_host, shape, wl.requests)
     kernels = {}
@@ -183,7 +198,6 @@ def main():
         if work[n]["flops"]:
             ent["TFLOP/s"] = round(work[n]["flops"] / (ms * 1e-3) / 1e12, 2)
         kernels[n] = ent
-    dominant = max(names, key=lambda n: per_call[n])
     if dominant in ("qkv", "attn", "score"):
         achieved = work[dominant]["flops"] / (per_call[dominant] * 1e-3) / 1e12
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(achieved, 2),
