@@ -270,6 +270,57 @@ def fuse_layer(k_chunks, v_chunks, deltas, q_probe, x_ctx, w_qkv, ratio, n_q_hea
                 k_patched=k_p, v_patched=v_p, o_sel=qz(o), lse=lse)
 
 
+# --------------------------------------------------------------------------
+# rest of the layer for the recomputed rows (next row after the six-call path)
+# --------------------------------------------------------------------------
+# Section 3.1, Phase 4 of the paper recomputes the selected tokens "layer by layer": after the sparse
+# attention their hidden states must pass through the remainder of the transformer block before the next
+# layer's projection.  The paper does not spell the block out; the model families it evaluates
+# (Llama-3.1, Qwen3, Mistral) all use the pre-norm block with a gated SiLU feed-forward written below.
+
+def rmsnorm(x: np.ndarray, weight: np.ndarray, eps: float) -> np.ndarray:
+    """y = x / sqrt(mean(x^2 over the last axis) + eps) * weight."""
+    x = np.asarray(x, dtype=F64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + F64(eps)) * np.asarray(weight, dtype=F64)
+
+
+def linear(x: np.ndarray, w: np.ndarray, residual: Optional[np.ndarray] = None) -> np.ndarray:
+    """y = x w^T (+ residual);  x [M, K], w [N, K] (one row per output feature)."""
+    y = np.asarray(x, dtype=F64) @ np.asarray(w, dtype=F64).T
+    if residual is not None:
+        y = y + np.asarray(residual, dtype=F64)
+    return y
+
+
+def swiglu(gate_up: np.ndarray) -> np.ndarray:
+    """silu(gate) * up for gate_up = [gate | up] along the last axis;  silu(g) = g / (1 + exp(-g))."""
+    gu = np.asarray(gate_up, dtype=F64)
+    f = gu.shape[-1] // 2
+    g, u = gu[..., :f], gu[..., f:]
+    return g / (1.0 + np.exp(-g)) * u
+
+
+def layer_tail(h_in: np.ndarray, o_rows: np.ndarray, w_o: np.ndarray, norm_weight: np.ndarray,
+               w_gate_up: np.ndarray, w_down: np.ndarray, eps: float, quantize=None) -> np.ndarray:
+    """Hidden states of the rows after the block, given their attention outputs.
+
+    h_in [M, d_model] block input (residual stream);  o_rows [M, H, d] attention output;
+    w_o [d_model, H d];  norm_weight [d_model];  w_gate_up [2 F, d_model] (gate rows, then up rows);
+    w_down [d_model, F].
+        h1 = h_in + o w_o^T;  h_out = h1 + (silu(n w_gate^T) * (n w_up^T)) w_down^T,  n = rmsnorm(h1).
+    `quantize` (optional) is applied to every stored intermediate, as the GPU path stores them in its
+    element type between calls.
+    """
+    q = quantize if quantize is not None else (lambda a: a)
+    m = o_rows.shape[0]
+    h1 = q(linear(o_rows.reshape(m, -1), w_o, h_in))
+    n = q(rmsnorm(h1, norm_weight, eps))
+    gu = q(linear(n, w_gate_up))
+    act = q(swiglu(gu))
+    return q(linear(act, w_down, h1))
+
+
 class PlantOps:
     """Backend handed to the workload assembler by tests: the oracle's own
     projection and key shift."""
