@@ -169,6 +169,31 @@ qcf_status qcf_recompute_attn(const qcf_layer_desc* desc, int32_t B,
                               const int32_t* ctx_pos0_dev, void* o_out, float* lse_out,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- rest of the layer for the recomputed rows (Section 3.1 Phase 4: the selected tokens are
+ * recomputed "layer by layer", so after the sparse attention their hidden states pass through the
+ * remainder of the transformer block before the next layer's projection.  The paper does not spell
+ * the block out; these are the pieces of the pre-norm block with a gated SiLU feed-forward that the
+ * model families it evaluates share).  Element type desc->dtype (only the dtype field of the
+ * descriptor is used), fp32 accumulation, results rounded once when stored.
+ *
+ * qcf_linear:  out[m, :] = x[m, :] . w^T (+ residual[m, :]);  x [M, K], w [N, K] (one row per
+ *   output feature), residual / out [M, N].  residual may be NULL, and may be the same buffer as out.
+ *   K and N must be multiples of 8.  Uses the MFMA path when dtype is bf16, K % 64 == 0, N % 128 == 0.
+ * qcf_rmsnorm: out[m, :] = x[m, :] / sqrt(mean_c x[m, c]^2 + eps) * weight[:];  x / out [M, cols],
+ *   weight [cols]; cols a multiple of 8; out may be the same buffer as x.
+ * qcf_swiglu:  out[m, f] = silu(gate_up[m, f]) * gate_up[m, F + f], silu(g) = g / (1 + exp(-g));
+ *   gate_up [M, 2F], out [M, F]; F a multiple of 8.
+ * One block for M rows:  h1 = linear(o, w_o, residual = h_in);  n = rmsnorm(h1);
+ *   h_out = linear(swiglu(linear(n, w_gate_up)), w_down, residual = h1). */
+size_t qcf_linear_workspace_bytes(const qcf_layer_desc* desc, int64_t M, int32_t K, int32_t N);
+qcf_status qcf_linear(const qcf_layer_desc* desc, const void* x, int64_t M, int32_t K,
+                      const void* w, int32_t N, const void* residual, void* out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+qcf_status qcf_rmsnorm(const qcf_layer_desc* desc, const void* x, const void* weight, double eps,
+                       int64_t M, int32_t cols, void* out, void* stream);
+qcf_status qcf_swiglu(const qcf_layer_desc* desc, const void* gate_up, int64_t M, int32_t F,
+                      void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

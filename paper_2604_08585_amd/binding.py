@@ -23,6 +23,7 @@ EXPORTS = [
     "qcf_recompute_qkv_workspace_bytes", "qcf_recompute_qkv",
     "qcf_scatter",
     "qcf_recompute_attn_workspace_bytes", "qcf_recompute_attn",
+    "qcf_linear_workspace_bytes", "qcf_linear", "qcf_rmsnorm", "qcf_swiglu",
 ]
 
 
@@ -85,6 +86,14 @@ def load_library() -> C.CDLL:
     lib.qcf_recompute_attn_workspace_bytes.argtypes = [dp, i32, i64, i64]
     lib.qcf_recompute_attn.restype = C.c_int
     lib.qcf_recompute_attn.argtypes = [dp, i32, vp, vp, vp, i64, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    lib.qcf_linear_workspace_bytes.restype = sz
+    lib.qcf_linear_workspace_bytes.argtypes = [dp, i64, i32, i32]
+    lib.qcf_linear.restype = C.c_int
+    lib.qcf_linear.argtypes = [dp, vp, i64, i32, vp, i32, vp, vp, vp, sz, vp]
+    lib.qcf_rmsnorm.restype = C.c_int
+    lib.qcf_rmsnorm.argtypes = [dp, vp, vp, dbl, i64, i32, vp, vp]
+    lib.qcf_swiglu.restype = C.c_int
+    lib.qcf_swiglu.argtypes = [dp, vp, i64, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -224,3 +233,25 @@ def qcf_recompute_attn(desc: LayerDesc, B: int, q_sel: torch.Tensor, sel_pos: to
     _check(lib.qcf_recompute_attn(C.byref(desc), B, _ptr(q_sel), _ptr(sel_pos), _ptr(sel_off), total_sel,
                                   _ptr(k_fused), _ptr(v_fused), _ptr(ctx_off), total_ctx, _ptr(ctx_pos0),
                                   _ptr(o_out), _ptr(lse_out), wp, wn, _stream()))
+
+
+def qcf_linear_workspace_bytes(desc: LayerDesc, M: int, K: int, N: int) -> int:
+    return int(load_library().qcf_linear_workspace_bytes(C.byref(desc), M, K, N))
+
+
+def qcf_linear(desc: LayerDesc, x: torch.Tensor, M: int, K: int, w: torch.Tensor, N: int,
+               residual: Optional[torch.Tensor], out: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(qcf_linear_workspace_bytes(desc, M, K, N), x.device)
+    wp, wn = _ws_args(workspace)
+    _check(lib.qcf_linear(C.byref(desc), _ptr(x), M, K, _ptr(w), N, _ptr(residual), _ptr(out), wp, wn, _stream()))
+
+
+def qcf_rmsnorm(desc: LayerDesc, x: torch.Tensor, weight: torch.Tensor, eps: float, M: int, cols: int,
+                out: torch.Tensor) -> None:
+    _check(load_library().qcf_rmsnorm(C.byref(desc), _ptr(x), _ptr(weight), float(eps), M, cols, _ptr(out), _stream()))
+
+
+def qcf_swiglu(desc: LayerDesc, gate_up: torch.Tensor, M: int, F: int, out: torch.Tensor) -> None:
+    _check(load_library().qcf_swiglu(C.byref(desc), _ptr(gate_up), M, F, _ptr(out), _stream()))

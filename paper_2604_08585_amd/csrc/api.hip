@@ -256,4 +256,60 @@ qcf_status qcf_recompute_attn(const qcf_layer_desc* desc, int32_t B, const void*
                      total_ctx, ctx_pos0_dev, o_out, lse_out, workspace, (hipStream_t)stream);
 }
 
+// ---- rest of the layer ------------------------------------------------------------
+static qcf_status check_dtype(const qcf_layer_desc* d) {
+  if (!d) return fail(QCF_ERR_INVALID_ARG, "layer descriptor is NULL");
+  if (d->dtype != QCF_DTYPE_F32 && d->dtype != QCF_DTYPE_BF16)
+    return fail(QCF_ERR_UNSUPPORTED, "dtype %d (supported: 0 = f32, 1 = bf16)", d->dtype);
+  return QCF_OK;
+}
+
+size_t qcf_linear_workspace_bytes(const qcf_layer_desc* desc, int64_t M, int32_t K, int32_t N) {
+  if (check_dtype(desc) != QCF_OK || M <= 0 || K <= 0 || N <= 0) return 0;
+  return linear_workspace(*desc, M, K, N);
+}
+
+qcf_status qcf_linear(const qcf_layer_desc* desc, const void* x, int64_t M, int32_t K, const void* w,
+                      int32_t N, const void* residual, void* out, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  QCF_TRY(check_dtype(desc));
+  if (M < 0) return fail(QCF_ERR_INVALID_ARG, "negative size");
+  if (M > kMaxRows) return fail(QCF_ERR_UNSUPPORTED, "too many rows");
+  if (K <= 0 || N <= 0 || K % 8 != 0 || N % 8 != 0)
+    return fail(QCF_ERR_INVALID_ARG, "K = %d and N = %d must be positive multiples of 8", K, N);
+  if (M == 0) return QCF_OK;
+  QCF_TRY(need_ptr(x, "x"));
+  QCF_TRY(need_ptr(w, "w"));
+  QCF_TRY(opt_ptr(residual, "residual"));
+  QCF_TRY(need_ptr(out, "out"));
+  QCF_TRY(need_ws(workspace, workspace_bytes, linear_workspace(*desc, M, K, N)));
+  return launch_linear(*desc, x, M, K, w, N, residual, out, workspace, (hipStream_t)stream);
+}
+
+qcf_status qcf_rmsnorm(const qcf_layer_desc* desc, const void* x, const void* weight, double eps, int64_t M,
+                       int32_t cols, void* out, void* stream) {
+  QCF_TRY(check_dtype(desc));
+  if (M < 0) return fail(QCF_ERR_INVALID_ARG, "negative size");
+  if (M > kMaxRows) return fail(QCF_ERR_UNSUPPORTED, "too many rows");
+  if (cols <= 0 || cols % 8 != 0) return fail(QCF_ERR_INVALID_ARG, "cols = %d must be a positive multiple of 8", cols);
+  if (!(eps >= 0.0) || !std::isfinite(eps)) return fail(QCF_ERR_INVALID_ARG, "eps must be finite and >= 0");
+  if (M == 0) return QCF_OK;
+  QCF_TRY(need_ptr(x, "x"));
+  QCF_TRY(need_ptr(weight, "weight"));
+  QCF_TRY(need_ptr(out, "out"));
+  return launch_rmsnorm(*desc, x, weight, eps, M, cols, out, (hipStream_t)stream);
+}
+
+qcf_status qcf_swiglu(const qcf_layer_desc* desc, const void* gate_up, int64_t M, int32_t F, void* out,
+                      void* stream) {
+  QCF_TRY(check_dtype(desc));
+  if (M < 0) return fail(QCF_ERR_INVALID_ARG, "negative size");
+  if (M > kMaxRows) return fail(QCF_ERR_UNSUPPORTED, "too many rows");
+  if (F <= 0 || F % 8 != 0) return fail(QCF_ERR_INVALID_ARG, "F = %d must be a positive multiple of 8", F);
+  if (M == 0) return QCF_OK;
+  QCF_TRY(need_ptr(gate_up, "gate_up"));
+  QCF_TRY(need_ptr(out, "out"));
+  return launch_swiglu(*desc, gate_up, M, F, out, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -205,6 +205,14 @@ qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const 
                        const int64_t* ctx_off, int64_t total_ctx, const int32_t* ctx_pos0, void* o,
                        float* lse, void* ws, hipStream_t st);
 
+size_t linear_workspace(const qcf_layer_desc& L, int64_t M, int32_t K, int32_t N);
+qcf_status launch_linear(const qcf_layer_desc& L, const void* x, int64_t M, int32_t K, const void* w, int32_t N,
+                         const void* residual, void* out, void* ws, hipStream_t st);
+qcf_status launch_rmsnorm(const qcf_layer_desc& L, const void* x, const void* weight, double eps, int64_t M,
+                          int32_t cols, void* out, hipStream_t st);
+qcf_status launch_swiglu(const qcf_layer_desc& L, const void* gate_up, int64_t M, int32_t F, void* out,
+                         hipStream_t st);
+
 // rotary table shared by rerope and qkv: cs[m * (d/2) + i] = (cos, sin)(angle_m * theta_i),
 // angles taken in float64.  `pos` gives one integer per row.
 qcf_status launch_rope_table(const int32_t* pos, int64_t M, int head_dim, double base, float2* cs,

@@ -118,6 +118,90 @@ __global__ __launch_bounds__(256) void qkv_rope_split_generic(const float* __res
   }
 }
 
+// out = y (+ residual), stored in the element type (generic path of the plain linear map)
+template <typename T>
+__global__ __launch_bounds__(256) void linear_finish_generic(const float* __restrict__ y, const T* residual,
+                                                             int64_t n, T* out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float v = y[i];
+  if (residual) v += Elem<T>::load(residual + i);
+  Elem<T>::store(out + i, v);
+}
+
+// ------------------------------------------------------------------ RMSNorm and gated SiLU (HBM bound)
+
+// One workgroup per row: every thread keeps its 16-byte vectors of the row in registers (up to kNormVecs),
+// the sum of squares goes through the waves and LDS in a fixed order, then the row is scaled and stored.
+constexpr int kNormVecs = 4;
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T* x, const T* __restrict__ weight, float eps, int cols,
+                                                      T* out) {
+  constexpr int VEC = Elem<T>::kVec;
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t row = blockIdx.x;
+  const T* xr = x + row * cols;
+  const int n_vec = cols / VEC;
+  u32x4 raw[kNormVecs];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < kNormVecs; ++i) {
+    const int v = tid + i * 256;
+    if (v < n_vec) {
+      raw[i] = *reinterpret_cast<const u32x4*>(xr + v * VEC);
+      float f[VEC];
+      Vec16<T>::unpack(raw[i], f);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) ss += f[e] * f[e];
+    }
+  }
+  for (int v = tid + kNormVecs * 256; v < n_vec; v += 256) {       // longer rows: the tail is read twice
+    float f[VEC];
+    Vec16<T>::unpack(*reinterpret_cast<const u32x4*>(xr + v * VEC), f);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) ss += f[e] * f[e];
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) ss += __shfl_xor(ss, d, 64);
+  if (lane == 0) red[wave] = ss;
+  __syncthreads();
+  const float scale = rsqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)cols + eps);
+  T* orow = out + row * cols;
+  auto emit = [&](int v, const u32x4& r) {
+    float f[VEC], g[VEC];
+    Vec16<T>::unpack(r, f);
+    Vec16<T>::unpack(*reinterpret_cast<const u32x4*>(weight + v * VEC), g);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) f[e] = f[e] * scale * g[e];
+    *reinterpret_cast<u32x4*>(orow + v * VEC) = Vec16<T>::pack(f);
+  };
+#pragma unroll
+  for (int i = 0; i < kNormVecs; ++i) {
+    const int v = tid + i * 256;
+    if (v < n_vec) emit(v, raw[i]);
+  }
+  for (int v = tid + kNormVecs * 256; v < n_vec; v += 256) emit(v, *reinterpret_cast<const u32x4*>(xr + v * VEC));
+}
+
+// out[m, f] = silu(gate_up[m, f]) * gate_up[m, F + f]; one 16-byte output vector per thread
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ gate_up, int64_t M, int F,
+                                                     T* __restrict__ out) {
+  constexpr int VEC = Elem<T>::kVec;
+  const int per_row = F / VEC;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * per_row) return;
+  const int64_t m = i / per_row;
+  const int c = (int)(i - m * per_row) * VEC;
+  float g[VEC], u[VEC];
+  Vec16<T>::unpack(*reinterpret_cast<const u32x4*>(gate_up + m * 2 * F + c), g);
+  Vec16<T>::unpack(*reinterpret_cast<const u32x4*>(gate_up + m * 2 * F + F + c), u);
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) g[e] = g[e] / (1.f + __expf(-g[e])) * u[e];
+  *reinterpret_cast<u32x4*>(out + m * F + c) = Vec16<T>::pack(g);
+}
+
 // ------------------------------------------------------------------ MFMA path (bf16)
 
 constexpr int kBK = 64;                  // contraction elements per LDS stage (rows of 128 bytes)
@@ -136,6 +220,9 @@ struct QkvArgs {
   bf16_t* q;
   bf16_t* k;
   bf16_t* v;
+  // plain linear map (qcf_linear): all H*D columns go to q without rotation; residual (may be NULL) is added
+  int plain;
+  const bf16_t* residual;
 };
 
 template <int TM, int TN, int WGM, int WGN>
@@ -162,7 +249,7 @@ struct OutTile {
 __device__ __forceinline__ OutTile out_tile_of(const QkvArgs& a, int col0) {
   const int q_cols = a.H * a.D, kv_cols = a.Hkv * a.D;
   OutTile o;
-  o.rotate = true;
+  o.rotate = !a.plain;
   if (col0 < q_cols) { o.out = a.q; o.out_cols = q_cols; o.out_col0 = col0; }
   else if (col0 < q_cols + kv_cols) { o.out = a.k; o.out_cols = kv_cols; o.out_col0 = col0 - q_cols; }
   else { o.out = a.v; o.out_cols = kv_cols; o.out_col0 = col0 - q_cols - kv_cols; o.rotate = false; }
@@ -210,7 +297,7 @@ __device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, in
     i0 = (e0 % a.D) / 2;
   }
   bool zero[NT];
-  u32x4 w4[NT][4];                                     // 8 (cos, sin) pairs per row
+  u32x4 w4[NT][4];                                     // 8 (cos, sin) pairs per row, or the row's 16 residual values
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int64_t m = m0 + r0 + t * RSTEP;
@@ -224,6 +311,10 @@ __device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, in
         const u32x4* my = reinterpret_cast<const u32x4*>(a.cs + m * half + i0);
 #pragma unroll
         for (int p = 0; p < 4; ++p) w4[t][p] = my[p];
+      } else if (a.residual) {
+        const bf16_t* res = a.residual + m * ot.out_cols + ot.out_col0;
+        w4[t][0] = *reinterpret_cast<const u32x4*>(res + e0);
+        w4[t][1] = *reinterpret_cast<const u32x4*>(res + e1);
       }
     }
   }
@@ -254,6 +345,12 @@ __device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, in
         o[ia] = f[ia] * wx - f[ib] * wy;
         o[ib] = f[ib] * wx + f[ia] * wy;
       }
+    } else if (a.residual) {
+      float res[16];
+      Vec16<bf16_t>::unpack(w4[t][0], res);
+      Vec16<bf16_t>::unpack(w4[t][1], res + 8);
+#pragma unroll
+      for (int p = 0; p < 16; ++p) o[p] = f[p] + res[p];
     } else {
 #pragma unroll
       for (int p = 0; p < 16; ++p) o[p] = f[p];
@@ -642,6 +739,7 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     a.d_model = L.d_model; a.H = H; a.Hkv = Hkv; a.D = D;
     a.m_tiles = 0; a.n_tiles = 0;
     a.q = static_cast<bf16_t*>(q); a.k = static_cast<bf16_t*>(k); a.v = static_cast<bf16_t*>(v);
+    a.plain = 0; a.residual = nullptr;
     // 256-row tiles when they still give every compute unit a workgroup, else 128-row tiles
     const int64_t tiles256 = ((M + 255) / 256) * (Ntot / kBN);
     // (the specialised kernel addresses x with 32-bit byte offsets)
@@ -672,6 +770,89 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
         static_cast<float*>(v));
   }
   return check_launch("qkv rope");
+}
+
+// ---- plain linear map, RMSNorm, gated SiLU (rest of the layer for the recomputed rows) -----------------
+
+static bool linear_uses_mfma(const qcf_layer_desc& L, int32_t K, int32_t N) {
+  return L.dtype == QCF_DTYPE_BF16 && K % kBK == 0 && N % kBN == 0;
+}
+
+size_t linear_workspace(const qcf_layer_desc& L, int64_t M, int32_t K, int32_t N) {
+  if (linear_uses_mfma(L, K, N)) return 0;
+  return align_up((size_t)M * N * sizeof(float), 256);
+}
+
+qcf_status launch_linear(const qcf_layer_desc& L, const void* x, int64_t M, int32_t K, const void* w, int32_t N,
+                         const void* residual, void* out, void* ws, hipStream_t st) {
+  if (linear_uses_mfma(L, K, N)) {
+    // the projection GEMM with one "query" output of N / 128 heads of 128 columns and no rotation
+    qcf_layer_desc LL = L;
+    LL.d_model = K; LL.n_q_heads = N / kBN; LL.n_kv_heads = 0; LL.head_dim = kBN; LL.rope_style = 0;
+    QkvArgs a;
+    a.x = static_cast<const bf16_t*>(x);
+    a.w = static_cast<const bf16_t*>(w);
+    a.gather = nullptr;
+    a.cs = nullptr;
+    a.x_rows = M;
+    a.M = M;
+    a.d_model = K; a.H = N / kBN; a.Hkv = 0; a.D = kBN;
+    a.m_tiles = 0; a.n_tiles = 0;
+    a.q = static_cast<bf16_t*>(out); a.k = nullptr; a.v = nullptr;
+    a.plain = 1;
+    a.residual = static_cast<const bf16_t*>(residual);
+    const int64_t tiles256 = ((M + 255) / 256) * (N / kBN);
+    if (tiles256 >= 200 && (uint64_t)M * (uint64_t)K * 2u < (1ull << 32)) return run_ws(LL, a, st);
+    if (tiles256 >= 200) return run_mfma<2, 4, 4, 1>(LL, a, st);
+    return run_mfma<2, 2, 2, 2>(LL, a, st);
+  }
+  float* y = static_cast<float*>(ws);
+  const int64_t mb = (M + 63) / 64;
+  const int nb = (N + 63) / 64;
+  const int64_t n = M * N;
+  if (mb > 0x7fffffff || nb > 65535 || (n + 255) / 256 > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "linear: grid too large");
+  const dim3 grid((unsigned)mb, (unsigned)nb), block(256);
+  if (L.dtype == QCF_DTYPE_BF16) {
+    qkv_gemm_generic<bf16_t><<<grid, block, 0, st>>>(static_cast<const bf16_t*>(x), M, nullptr, M,
+                                                     static_cast<const bf16_t*>(w), K, N, y);
+    QCF_TRY_LAUNCH("linear gemm");
+    linear_finish_generic<bf16_t><<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(
+        y, static_cast<const bf16_t*>(residual), n, static_cast<bf16_t*>(out));
+  } else {
+    qkv_gemm_generic<float><<<grid, block, 0, st>>>(static_cast<const float*>(x), M, nullptr, M,
+                                                    static_cast<const float*>(w), K, N, y);
+    QCF_TRY_LAUNCH("linear gemm");
+    linear_finish_generic<float><<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(
+        y, static_cast<const float*>(residual), n, static_cast<float*>(out));
+  }
+  return check_launch("linear finish");
+}
+
+qcf_status launch_rmsnorm(const qcf_layer_desc& L, const void* x, const void* weight, double eps, int64_t M,
+                          int32_t cols, void* out, hipStream_t st) {
+  if (M > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "rmsnorm: too many rows");
+  const dim3 grid((unsigned)M), block(256);
+  if (L.dtype == QCF_DTYPE_BF16)
+    rmsnorm_kernel<bf16_t><<<grid, block, 0, st>>>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(weight),
+                                                   (float)eps, cols, static_cast<bf16_t*>(out));
+  else
+    rmsnorm_kernel<float><<<grid, block, 0, st>>>(static_cast<const float*>(x), static_cast<const float*>(weight),
+                                                  (float)eps, cols, static_cast<float*>(out));
+  return check_launch("rmsnorm");
+}
+
+qcf_status launch_swiglu(const qcf_layer_desc& L, const void* gate_up, int64_t M, int32_t F, void* out,
+                         hipStream_t st) {
+  const int vec = 16 / elem_size(L.dtype);
+  const int64_t blocks = (M * (F / vec) + 255) / 256;
+  if (blocks > 0x7fffffff) return fail(QCF_ERR_UNSUPPORTED, "swiglu: too many elements");
+  if (L.dtype == QCF_DTYPE_BF16)
+    swiglu_kernel<bf16_t><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(static_cast<const bf16_t*>(gate_up), M, F,
+                                                                        static_cast<bf16_t*>(out));
+  else
+    swiglu_kernel<float><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(static_cast<const float*>(gate_up), M, F,
+                                                                       static_cast<float*>(out));
+  return check_launch("swiglu");
 }
 
 }  // namespace qcf

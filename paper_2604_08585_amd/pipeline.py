@@ -193,3 +193,35 @@ class HipPlantOps:
         qb.qcf_rerope(desc32, table, 1, n, out, None)
         torch.cuda.synchronize()
         return out.cpu().numpy()
+
+
+# ------------------------------------------------------------------ rest of the layer
+
+@dataclasses.dataclass
+class TailWeights:
+    """Device weights of the part of a pre-norm block that follows the attention."""
+    w_o: torch.Tensor          # [d_model, H d]
+    norm_weight: torch.Tensor  # [d_model]
+    w_gate_up: torch.Tensor    # [2 F, d_model], gate rows then up rows
+    w_down: torch.Tensor       # [d_model, F]
+    eps: float
+
+
+def layer_tail(desc, h_in: torch.Tensor, o_rows: torch.Tensor, tw: TailWeights) -> torch.Tensor:
+    """Hidden states of the recomputed rows after the block: h1 = h_in + o w_o^T,
+    h_out = h1 + (silu(n w_gate^T) * (n w_up^T)) w_down^T with n = rmsnorm(h1).  Five library calls."""
+    M, dm = h_in.shape
+    hd = tw.w_o.shape[1]
+    F2 = tw.w_gate_up.shape[0]
+    dt, dev = h_in.dtype, h_in.device
+    h1 = torch.empty((M, dm), dtype=dt, device=dev)
+    qb.qcf_linear(desc, o_rows.reshape(M, hd), M, hd, tw.w_o, dm, h_in, h1)
+    n = torch.empty_like(h1)
+    qb.qcf_rmsnorm(desc, h1, tw.norm_weight, tw.eps, M, dm, n)
+    gu = torch.empty((M, F2), dtype=dt, device=dev)
+    qb.qcf_linear(desc, n, M, dm, tw.w_gate_up, F2, None, gu)
+    act = torch.empty((M, F2 // 2), dtype=dt, device=dev)
+    qb.qcf_swiglu(desc, gu, M, F2 // 2, act)
+    out = torch.empty_like(h1)
+    qb.qcf_linear(desc, act, M, F2 // 2, tw.w_down, dm, h1, out)
+    return out

@@ -21,7 +21,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = qb.load_library()
     names = declared_symbols()
-    assert len(names) == 15 and set(names) == set(qb.EXPORTS)
+    assert len(names) == 19 and set(names) == set(qb.EXPORTS)
     for n in names:
         assert hasattr(lib, n), n
     assert lib.qcf_version() >= 100
@@ -77,6 +77,17 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.qcf_recompute_qkv(C.byref(d), fake, -1, None, 4, fake, fake, fake, fake, fake, fake, 1 << 20, None) == 1
     assert lib.qcf_recompute_qkv(C.byref(d), fake, 2, None, 4, fake, fake, fake, fake, fake, fake, 1 << 20, None) == 1
     assert lib.qcf_scatter(C.byref(d), fake, fake, fake, 4, fake, None, 8, None) == 1
+    # rest-of-the-layer calls: sizes must be multiples of 8, the f32 / odd-shape path needs its workspace
+    assert lib.qcf_linear(C.byref(d), fake, 4, 20, fake, 64, None, fake, None, 0, None) == 1
+    assert lib.qcf_linear(C.byref(d), fake, 4, 64, fake, 128, None, None, None, 0, None) == 1
+    assert lib.qcf_linear_workspace_bytes(C.byref(_desc(dtype="bf16")), 4, 64, 128) == 0   # MFMA-shaped bf16: none
+    need_l = lib.qcf_linear_workspace_bytes(C.byref(d), 4, 24, 40)
+    assert need_l >= 4 * 40 * 4
+    assert lib.qcf_linear(C.byref(d), fake, 4, 24, fake, 40, None, fake, fake, need_l - 1, None) == 3
+    assert lib.qcf_rmsnorm(C.byref(d), fake, fake, 1e-5, 4, 100, fake, None) == 1
+    assert lib.qcf_rmsnorm(C.byref(d), fake, fake, -1.0, 4, 64, fake, None) == 1
+    assert lib.qcf_swiglu(C.byref(d), fake, 4, 12, fake, None) == 1
+    assert lib.qcf_swiglu(C.byref(bad), fake, 4, 16, fake, None) == 2
 
 
 def test_empty_work_is_ok_and_launches_nothing():
@@ -89,6 +100,9 @@ def test_empty_work_is_ok_and_launches_nothing():
     assert lib.qcf_scatter(C.byref(d), None, None, None, 0, None, None, 10, None) == 0
     assert lib.qcf_recompute_attn(C.byref(d), 1, None, None, None, 0, None, None, None, 10, None, None, None,
                                   None, 0, None) == 0
+    assert lib.qcf_linear(C.byref(d), None, 0, 64, None, 128, None, None, None, 0, None) == 0
+    assert lib.qcf_rmsnorm(C.byref(d), None, None, 1e-5, 0, 64, None, None) == 0
+    assert lib.qcf_swiglu(C.byref(d), None, 0, 64, None, None) == 0
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
