@@ -34,6 +34,9 @@ def parse_args():
     p.add_argument("--copies", type=int, default=6, help="independent buffer sets cycled through")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-sample-rows", type=int, default=256)
+    p.add_argument("--no-tail", action="store_true",
+                   help="skip the extra leg that times the rest of the layer (o_proj, RMSNorm, gated feed-forward)")
+    p.add_argument("--d-ff", type=int, default=14336, help="feed-forward width of the extra leg")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     return p.parse_args()
@@ -100,6 +103,59 @@ def cpu_baseline(cfg, ratio, sample_rows):
             "sample": f"config {cfg}, ratio {ratio}: rerope/score/select/scatter in full; qkv and attn on "
                       f"{len(rows)} of {n} selected rows, their time scaled by {scale:.1f}",
             "ms_per_call": {k: round(v * 1e3, 2) for k, v in t.items()}}
+
+
+def tail_leg(L, shape, d_ff, dev, steps=20):
+    """Not part of the metric: the rest of the block for the N recomputed rows (random weights of the
+    8B-shaped block), five library calls, timed call by call with events."""
+    import numpy as np
+    import torch
+    from paper_2604_08585_amd import binding as qb
+    from paper_2604_08585_amd import pipeline
+    M, dm, hd = L.total_sel, shape.d_model, shape.n_q_heads * shape.head_dim
+    dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    g = torch.Generator(device=dev).manual_seed(7)
+
+    def w(rows, cols, std):
+        return (torch.randn((rows, cols), generator=g, device=dev) * std).to(dt)
+    tw = pipeline.TailWeights(w(dm, hd, hd ** -0.5), torch.ones(dm, dtype=dt, device=dev), w(2 * d_ff, dm, dm ** -0.5),
+                              w(dm, d_ff, d_ff ** -0.5), 1e-5)
+    h_in = w(M, dm, 1.0)
+    o = L.o_sel[:M].reshape(M, hd)
+    bufs = dict(h1=torch.empty((M, dm), dtype=dt, device=dev), n=torch.empty((M, dm), dtype=dt, device=dev),
+                gu=torch.empty((M, 2 * d_ff), dtype=dt, device=dev), act=torch.empty((M, d_ff), dtype=dt, device=dev),
+                out=torch.empty((M, dm), dtype=dt, device=dev))
+    calls = [
+        ("o_proj", lambda: qb.qcf_linear(L.desc, o, M, hd, tw.w_o, dm, h_in, bufs["h1"]), 2 * M * hd * dm),
+        ("rmsnorm", lambda: qb.qcf_rmsnorm(L.desc, bufs["h1"], tw.norm_weight, tw.eps, M, dm, bufs["n"]), 0),
+        ("gate_up", lambda: qb.qcf_linear(L.desc, bufs["n"], M, dm, tw.w_gate_up, 2 * d_ff, None, bufs["gu"]),
+         2 * M * dm * 2 * d_ff),
+        ("swiglu", lambda: qb.qcf_swiglu(L.desc, bufs["gu"], M, d_ff, bufs["act"]), 0),
+        ("down", lambda: qb.qcf_linear(L.desc, bufs["act"], M, d_ff, tw.w_down, dm, bufs["h1"], bufs["out"]),
+         2 * M * d_ff * dm),
+    ]
+    for _ in range(3):
+        for _, fn, _ in calls:
+            fn()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
+          for _ in range(steps)]
+    torch.cuda.synchronize()
+    for i in range(steps):
+        for j, (_, fn, _) in enumerate(calls):
+            ev[i][j][0].record()
+            fn()
+            ev[i][j][1].record()
+    torch.cuda.synchronize()
+    res, total = {}, 0.0
+    for j, (name, _, flops) in enumerate(calls):
+        ms = float(np.mean([ev[i][j][0].elapsed_time(ev[i][j][1]) for i in range(steps)]))
+        total += ms
+        res[name] = {"ms": round(ms, 5)}
+        if flops:
+            res[name]["TFLOP/s"] = round(flops / (ms * 1e-3) / 1e12, 1)
+    res["total_ms"] = round(total, 5)
+    res["shape"] = f"M={M}, d_model={dm}, d_ff={d_ff}"
+    return res
 
 
 def load_traffic(kernel, workload):
@@ -225,6 +281,8 @@ def main():
         "analysis_ms": round(per_call["score"] + per_call["select"], 5),
         "reconstruction_ms": round(per_call["rerope"] + per_call["qkv"] + per_call["scatter"] + per_call["attn"], 5),
     }
+    if not args.no_tail:
+        out["next_rows"] = {"layer_tail": tail_leg(layers[0], shape, args.d_ff, dev)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.ratio, args.cpu_sample_rows)
     print(json.dumps(out))

@@ -647,6 +647,24 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
   store_tile<C::BM, C::NTHR, STYLE>(a, sC, m0, ot, tid);
 }
 
+// 256-row tiles (load/compute-split kernel) or 128-row tiles?  Both run one workgroup per compute unit, so
+// the launch takes (rounds of workgroups) x (time of one workgroup); the per-k-tile and fixed costs are the
+// measured ones of the two kernels on MI355X (microseconds).
+bool prefer_256_rows(int64_t M, int n_col_tiles, int K) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+  }
+  const double k_tiles = (double)K / kBK;
+  const int64_t wg256 = ((M + 255) / 256) * n_col_tiles, wg128 = ((M + 127) / 128) * n_col_tiles;
+  const double t256 = (double)((wg256 + cus - 1) / cus) * (0.8 * k_tiles + 15.0);
+  const double t128 = (double)((wg128 + cus - 1) / cus) * (0.7 * k_tiles + 10.0);
+  return t256 < t128;
+}
+
 bool use_mfma(const qcf_layer_desc& L) {
   return L.dtype == QCF_DTYPE_BF16 && L.d_model % kBK == 0 && (L.n_kv_heads * L.head_dim) % kBN == 0;
 }
@@ -740,11 +758,10 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     a.m_tiles = 0; a.n_tiles = 0;
     a.q = static_cast<bf16_t*>(q); a.k = static_cast<bf16_t*>(k); a.v = static_cast<bf16_t*>(v);
     a.plain = 0; a.residual = nullptr;
-    // 256-row tiles when they still give every compute unit a workgroup, else 128-row tiles
-    const int64_t tiles256 = ((M + 255) / 256) * (Ntot / kBN);
+    const bool big = prefer_256_rows(M, Ntot / kBN, L.d_model);
     // (the specialised kernel addresses x with 32-bit byte offsets)
-    if (tiles256 >= 200 && (uint64_t)x_rows * (uint64_t)L.d_model * 2u < (1ull << 32)) return run_ws(L, a, st);
-    if (tiles256 >= 200) return run_mfma<2, 4, 4, 1>(L, a, st);
+    if (big && (uint64_t)x_rows * (uint64_t)L.d_model * 2u < (1ull << 32)) return run_ws(L, a, st);
+    if (big) return run_mfma<2, 4, 4, 1>(L, a, st);
     return run_mfma<2, 2, 2, 2>(L, a, st);
   }
   float* y = reinterpret_cast<float*>(static_cast<char*>(ws) + cs_bytes(L, M));
@@ -801,9 +818,9 @@ qcf_status launch_linear(const qcf_layer_desc& L, const void* x, int64_t M, int3
     a.q = static_cast<bf16_t*>(out); a.k = nullptr; a.v = nullptr;
     a.plain = 1;
     a.residual = static_cast<const bf16_t*>(residual);
-    const int64_t tiles256 = ((M + 255) / 256) * (N / kBN);
-    if (tiles256 >= 200 && (uint64_t)M * (uint64_t)K * 2u < (1ull << 32)) return run_ws(LL, a, st);
-    if (tiles256 >= 200) return run_mfma<2, 4, 4, 1>(LL, a, st);
+    const bool big = prefer_256_rows(M, N / kBN, K);
+    if (big && (uint64_t)M * (uint64_t)K * 2u < (1ull << 32)) return run_ws(LL, a, st);
+    if (big) return run_mfma<2, 4, 4, 1>(LL, a, st);
     return run_mfma<2, 2, 2, 2>(LL, a, st);
   }
   float* y = static_cast<float*>(ws);
