@@ -194,6 +194,19 @@ qcf_status qcf_rmsnorm(const qcf_layer_desc* desc, const void* x, const void* we
 qcf_status qcf_swiglu(const qcf_layer_desc* desc, const void* gate_up, int64_t M, int32_t F,
                       void* out, void* stream);
 
+/* ---- anchor extraction (Section 3.1 Phase 1, offline: for every precomputed chunk "a minor fraction
+ * of tokens with the highest key-norm values" is kept as a compressed summary).  The paper does not say
+ * which heads enter the norm; here norm[t] = sqrt(sum over the KV heads and elements of k[t]^2) of the
+ * layer at hand.  k [rows, H_kv, d]; norm [rows] float32.  The anchors of a set of chunks are then
+ * qcf_select(B = number of chunks, score = norm, ctx_off = chunk boundaries, sel_off = anchors per
+ * chunk) followed by qcf_gather of the K/V rows. */
+qcf_status qcf_key_norm(const qcf_layer_desc* desc, const void* k, int64_t rows, float* norm, void* stream);
+/* Row m of k_out / v_out <- row src_rows[m] of k_src / v_src (rows of H_kv * d elements); an index
+ * outside [0, total_rows) gives a zero row.  v_src and v_out may both be NULL.  The inverse of qcf_scatter. */
+qcf_status qcf_gather(const qcf_layer_desc* desc, const void* k_src, const void* v_src,
+                      const int32_t* src_rows_dev, int64_t M, int64_t total_rows, void* k_out, void* v_out,
+                      void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -321,6 +321,26 @@ def layer_tail(h_in: np.ndarray, o_rows: np.ndarray, w_o: np.ndarray, norm_weigh
     return q(linear(act, w_down, h1))
 
 
+# --------------------------------------------------------------------------
+# anchor extraction (offline, per chunk)
+# --------------------------------------------------------------------------
+# Section 3.1, Phase 1 of the paper keeps, for every precomputed chunk, a small fraction of its tokens - the ones
+# with the largest key norm - as a compressed summary ("anchors").  The paper does not say which heads enter the
+# norm; reading taken here: the Euclidean norm of the token's key over all KV heads of the layer at hand.
+
+def key_norm(k: np.ndarray) -> np.ndarray:
+    """norm[t] = sqrt(sum over heads and elements of k[t]^2);  k [T, H_kv, d]."""
+    k = np.asarray(k, dtype=F64)
+    return np.sqrt(np.sum(k * k, axis=(1, 2)))
+
+
+def extract_anchors(k_chunk: np.ndarray, v_chunk: np.ndarray, n: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Indices (ascending; ties to the lower index) of the n tokens of the chunk with the largest key norm,
+    and their K and V rows."""
+    idx = select(key_norm(k_chunk), n)
+    return idx, np.asarray(k_chunk)[idx], np.asarray(v_chunk)[idx]
+
+
 class PlantOps:
     """Backend handed to the workload assembler by tests: the oracle's own
     projection and key shift."""

@@ -24,6 +24,7 @@ EXPORTS = [
     "qcf_scatter",
     "qcf_recompute_attn_workspace_bytes", "qcf_recompute_attn",
     "qcf_linear_workspace_bytes", "qcf_linear", "qcf_rmsnorm", "qcf_swiglu",
+    "qcf_key_norm", "qcf_gather",
 ]
 
 
@@ -94,6 +95,10 @@ def load_library() -> C.CDLL:
     lib.qcf_rmsnorm.argtypes = [dp, vp, vp, dbl, i64, i32, vp, vp]
     lib.qcf_swiglu.restype = C.c_int
     lib.qcf_swiglu.argtypes = [dp, vp, i64, i32, vp, vp]
+    lib.qcf_key_norm.restype = C.c_int
+    lib.qcf_key_norm.argtypes = [dp, vp, i64, vp, vp]
+    lib.qcf_gather.restype = C.c_int
+    lib.qcf_gather.argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -255,3 +260,13 @@ def qcf_rmsnorm(desc: LayerDesc, x: torch.Tensor, weight: torch.Tensor, eps: flo
 
 def qcf_swiglu(desc: LayerDesc, gate_up: torch.Tensor, M: int, F: int, out: torch.Tensor) -> None:
     _check(load_library().qcf_swiglu(C.byref(desc), _ptr(gate_up), M, F, _ptr(out), _stream()))
+
+
+def qcf_key_norm(desc: LayerDesc, k: torch.Tensor, rows: int, norm: torch.Tensor) -> None:
+    _check(load_library().qcf_key_norm(C.byref(desc), _ptr(k), rows, _ptr(norm), _stream()))
+
+
+def qcf_gather(desc: LayerDesc, k_src: torch.Tensor, v_src: Optional[torch.Tensor], src_rows: torch.Tensor, M: int,
+               total_rows: int, k_out: torch.Tensor, v_out: Optional[torch.Tensor]) -> None:
+    _check(load_library().qcf_gather(C.byref(desc), _ptr(k_src), _ptr(v_src), _ptr(src_rows), M, total_rows,
+                                     _ptr(k_out), _ptr(v_out), _stream()))

@@ -312,4 +312,31 @@ qcf_status qcf_swiglu(const qcf_layer_desc* desc, const void* gate_up, int64_t M
   return launch_swiglu(*desc, gate_up, M, F, out, (hipStream_t)stream);
 }
 
+// ---- anchor extraction ------------------------------------------------------------
+qcf_status qcf_key_norm(const qcf_layer_desc* desc, const void* k, int64_t rows, float* norm, void* stream) {
+  QCF_TRY(check_desc(desc));
+  if (rows < 0) return fail(QCF_ERR_INVALID_ARG, "negative size");
+  if (rows > kMaxRows) return fail(QCF_ERR_UNSUPPORTED, "too many rows");
+  if (rows == 0) return QCF_OK;
+  QCF_TRY(need_ptr(k, "k"));
+  QCF_TRY(need_idx_ptr(norm, "norm"));
+  return launch_key_norm(*desc, k, rows, norm, (hipStream_t)stream);
+}
+
+qcf_status qcf_gather(const qcf_layer_desc* desc, const void* k_src, const void* v_src,
+                      const int32_t* src_rows_dev, int64_t M, int64_t total_rows, void* k_out, void* v_out,
+                      void* stream) {
+  QCF_TRY(check_desc(desc));
+  if (M < 0 || total_rows < 0) return fail(QCF_ERR_INVALID_ARG, "negative size");
+  if (M > kMaxRows || total_rows > kMaxRows) return fail(QCF_ERR_UNSUPPORTED, "too many rows");
+  if (M == 0) return QCF_OK;
+  QCF_TRY(need_ptr(k_src, "k_src"));
+  QCF_TRY(need_ptr(k_out, "k_out"));
+  QCF_TRY(need_idx_ptr(src_rows_dev, "src_rows_dev"));
+  if ((v_src == nullptr) != (v_out == nullptr)) return fail(QCF_ERR_INVALID_ARG, "v_src and v_out must both be given or both be NULL");
+  QCF_TRY(opt_ptr(v_src, "v_src"));
+  QCF_TRY(opt_ptr(v_out, "v_out"));
+  return launch_gather(*desc, k_src, v_src, src_rows_dev, M, total_rows, k_out, v_out, (hipStream_t)stream);
+}
+
 }  // extern "C"

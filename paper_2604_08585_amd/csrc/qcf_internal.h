@@ -199,6 +199,10 @@ qcf_status launch_scatter(const qcf_layer_desc& L, const void* k_new, const void
                           const int32_t* rows, int64_t M, void* kf, void* vf, int64_t total_rows,
                           hipStream_t st);
 
+qcf_status launch_gather(const qcf_layer_desc& L, const void* k_src, const void* v_src, const int32_t* rows,
+                         int64_t M, int64_t src_rows, void* k_out, void* v_out, hipStream_t st);
+qcf_status launch_key_norm(const qcf_layer_desc& L, const void* k, int64_t rows, float* norm, hipStream_t st);
+
 size_t attn_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_sel, int64_t total_ctx);
 qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const int32_t* sel_pos,
                        const int64_t* sel_off, int64_t total_sel, const void* k, const void* v,

@@ -225,3 +225,26 @@ def layer_tail(desc, h_in: torch.Tensor, o_rows: torch.Tensor, tw: TailWeights) 
     out = torch.empty_like(h1)
     qb.qcf_linear(desc, act, M, F2 // 2, tw.w_down, dm, h1, out)
     return out
+
+
+# ------------------------------------------------------------------ anchor extraction (offline)
+
+def extract_anchors(desc, k: torch.Tensor, v: torch.Tensor, chunk_lens: List[int], n_per_chunk: List[int]):
+    """For chunks stored back to back in k / v [sum len, H_kv, d]: the n_c tokens of chunk c with the largest key
+    norm.  Returns (rows into k / v, ascending inside each chunk; anchor K rows; anchor V rows).  Three library
+    calls: key norm, Top-N per chunk (the selection kernel with one "request" per chunk), gather."""
+    dev = k.device
+    rows = int(sum(chunk_lens))
+    n_per_chunk = [min(int(n), int(l)) for n, l in zip(n_per_chunk, chunk_lens)]
+    total = int(sum(n_per_chunk))
+    norm = torch.empty(max(rows, 1), dtype=torch.float32, device=dev)
+    qb.qcf_key_norm(desc, k, rows, norm)
+    ctx_off = torch.tensor(np.concatenate([[0], np.cumsum(chunk_lens)]), dtype=torch.int64, device=dev)
+    sel_off = torch.tensor(np.concatenate([[0], np.cumsum(n_per_chunk)]), dtype=torch.int64, device=dev)
+    idx = torch.empty(max(total, 1), dtype=torch.int32, device=dev)
+    row = torch.empty(max(total, 1), dtype=torch.int32, device=dev)
+    qb.qcf_select(len(chunk_lens), norm, ctx_off, rows, sel_off, total, None, idx, row, None)
+    ak = torch.empty((max(total, 1),) + tuple(k.shape[1:]), dtype=k.dtype, device=dev)
+    av = torch.empty_like(ak)
+    qb.qcf_gather(desc, k, v, row, total, rows, ak, av)
+    return row[:total], ak[:total], av[:total]

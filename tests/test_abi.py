@@ -21,7 +21,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = qb.load_library()
     names = declared_symbols()
-    assert len(names) == 19 and set(names) == set(qb.EXPORTS)
+    assert len(names) == 21 and set(names) == set(qb.EXPORTS)
     for n in names:
         assert hasattr(lib, n), n
     assert lib.qcf_version() >= 100
@@ -88,6 +88,8 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.qcf_rmsnorm(C.byref(d), fake, fake, -1.0, 4, 64, fake, None) == 1
     assert lib.qcf_swiglu(C.byref(d), fake, 4, 12, fake, None) == 1
     assert lib.qcf_swiglu(C.byref(bad), fake, 4, 16, fake, None) == 2
+    assert lib.qcf_key_norm(C.byref(d), None, 4, fake, None) == 1
+    assert lib.qcf_gather(C.byref(d), fake, fake, fake, 4, 10, fake, None, None) == 1
 
 
 def test_empty_work_is_ok_and_launches_nothing():
@@ -103,6 +105,8 @@ def test_empty_work_is_ok_and_launches_nothing():
     assert lib.qcf_linear(C.byref(d), None, 0, 64, None, 128, None, None, None, 0, None) == 0
     assert lib.qcf_rmsnorm(C.byref(d), None, None, 1e-5, 0, 64, None, None) == 0
     assert lib.qcf_swiglu(C.byref(d), None, 0, 64, None, None) == 0
+    assert lib.qcf_key_norm(C.byref(d), None, 0, None, None) == 0
+    assert lib.qcf_gather(C.byref(d), None, None, None, 0, 10, None, None, None) == 0
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):

@@ -150,3 +150,43 @@ def test_query_rows_run_as_extra_recomputed_rows():
     ro, _ = orc.recompute_attn(qz(rq), rows, rkf, rvf)
     assert_close(to_np(o), ro, "bf16", "O of context + query rows")
     assert_close(to_np(dk), rkf, "bf16", "fused K with query rows appended")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_anchor_extraction(dtype):
+    """Key norm, per-chunk Top-N by norm and the gather of the anchor rows against the oracle."""
+    rng = np.random.default_rng(45)
+    sh = (inputs.LayerShape(256, 4, 2, 64, 10000.0, "f32", 0) if dtype == "f32"
+          else inputs.LayerShape(4096, 32, 8, 128, 500000.0, "bf16", 0))
+    dt = inputs.torch_dtype(dtype)
+    lens = [300, 1, 517, 64, 1000]
+    n_anchor = [12, 1, 21, 0, 40]
+    ks = [rnd(rng, (n, sh.n_kv_heads, sh.head_dim), dtype) for n in lens]
+    vs = [rnd(rng, (n, sh.n_kv_heads, sh.head_dim), dtype) for n in lens]
+    say(f"anchors {dtype}: chunks {lens}, anchors {n_anchor}")
+    desc = qb.make_desc(sh)
+    k_all, v_all = to_dev(np.concatenate(ks), dt), to_dev(np.concatenate(vs), dt)
+    rows, ak, av = pipeline.extract_anchors(desc, k_all, v_all, lens, n_anchor)
+    norm = torch.empty(sum(lens), dtype=torch.float32, device=DEV)
+    qb.qcf_key_norm(desc, k_all, sum(lens), norm)
+    torch.cuda.synchronize()
+    ref_norm = np.concatenate([orc.key_norm(k) for k in ks])
+    assert np.all(np.abs(to_np(norm) - ref_norm) <= 2e-6 * ref_norm)
+    got = rows.cpu().numpy().astype(np.int64)
+    off, pos = 0, 0
+    from gpu_util import assert_indices_match
+    for c, n in enumerate(lens):
+        na = n_anchor[c]
+        mine = got[pos:pos + na] - off
+        # exact indices unless two norms are closer than the fp32 rounding of the norm
+        assert_indices_match(mine, orc.key_norm(ks[c]), na, f"chunk {c}")
+        assert np.array_equal(to_np(ak[pos:pos + na]), ks[c][mine]) and np.array_equal(to_np(av[pos:pos + na]), vs[c][mine])
+        off += n
+        pos += na
+    assert pos == len(got)
+    # an index outside the source gives a zero row
+    bad = i32([5, -1, sum(lens), 7])
+    ko = torch.full((4, sh.n_kv_heads, sh.head_dim), 3.0, dtype=dt, device=DEV)
+    qb.qcf_gather(desc, k_all, None, bad, 4, sum(lens), ko, None)
+    torch.cuda.synchronize()
+    assert torch.equal(ko[0], k_all[5]) and torch.equal(ko[3], k_all[7]) and float(ko[1:3].abs().max()) == 0.0

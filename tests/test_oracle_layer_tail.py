@@ -101,3 +101,30 @@ def test_query_rows_as_extra_recomputed_rows_equal_dense_prefill():
     dense = F.scaled_dot_product_attention(_t(q).permute(1, 0, 2)[None], _t(np.repeat(k, rep, axis=1)).permute(1, 0, 2)[None],
                                            _t(np.repeat(v, rep, axis=1)).permute(1, 0, 2)[None], is_causal=True)[0]
     assert np.allclose(o_q, dense.permute(1, 0, 2).numpy()[T:], atol=1e-11)
+
+
+# ---------------------------------------------------------------- anchor extraction
+
+def test_key_norm_closed_forms():
+    r = _rng(7)
+    k = r.standard_normal((9, 3, 8))
+    n = orc.key_norm(k)
+    assert np.allclose(n, np.linalg.norm(k.reshape(9, -1), axis=1), atol=1e-13)       # heads concatenated
+    assert np.allclose(orc.key_norm(-2.5 * k), 2.5 * n)
+    e = np.zeros((2, 3, 8)); e[0, 1, 4] = -3.0; e[1, 0, 0] = 3.0; e[1, 2, 7] = 4.0
+    assert np.allclose(orc.key_norm(e), [3.0, 5.0])
+    # heads add in quadrature
+    assert np.allclose(n ** 2, sum(orc.key_norm(k[:, h:h + 1]) ** 2 for h in range(3)))
+
+
+def test_extract_anchors_picks_the_largest_norms():
+    r = _rng(8)
+    k, v = r.standard_normal((50, 2, 4)), r.standard_normal((50, 2, 4))
+    k[[7, 30, 41]] *= 10.0
+    idx, ak, av = orc.extract_anchors(k, v, 3)
+    assert list(idx) == [7, 30, 41]
+    assert np.array_equal(ak, k[[7, 30, 41]]) and np.array_equal(av, v[[7, 30, 41]])
+    norms = np.linalg.norm(k.reshape(50, -1), axis=1)
+    idx6, _, _ = orc.extract_anchors(k, v, 6)
+    assert sorted(idx6) == sorted(np.argsort(-norms, kind="stable")[:6])
+    assert len(orc.extract_anchors(k, v, 0)[0]) == 0
