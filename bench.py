@@ -158,6 +158,45 @@ def tail_leg(L, shape, d_ff, dev, steps=20):
     return res
 
 
+def pipeline_leg(L, chunk_lens, n_layers=8, reps=3):
+    """Not part of the metric: reconstruction layers (rerope, qkv, scatter, attn) whose chunk caches come from
+    pinned host memory over a copy stream, double-buffered, against the same layers with resident caches and
+    against the copies alone.  This is the PCIe-inclusive per-layer time."""
+    import torch
+    from paper_2604_08585_amd import pipeline
+    host = pipeline.host_chunk_caches(L, seed=11, n_layers=n_layers)
+    st = pipeline.ChunkStreamer(L, chunk_lens, host)
+    mib = sum(h.numel() * h.element_size() for h in host[0]) / 2 ** 20
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / (reps * n_layers)
+
+    def resident():
+        for _ in range(n_layers):
+            pipeline.enqueue_layer(L, critical=False)
+
+    def copies():
+        with torch.cuda.stream(st.copy_stream):
+            for i in range(n_layers):
+                st.stage[i % 2][0].copy_(host[i][0], non_blocking=True)
+                st.stage[i % 2][1].copy_(host[i][1], non_blocking=True)
+        st.copy_stream.synchronize()
+
+    res = {"layers": n_layers, "chunk_cache_MiB_per_layer": round(mib, 1),
+           "resident_ms_per_layer": round(timed(resident), 5),
+           "copy_only_ms_per_layer": round(timed(copies), 5),
+           "streamed_ms_per_layer": round(timed(lambda: st.run(n_layers)), 5),
+           "serial_ms_per_layer": round(timed(lambda: st.run(n_layers, overlap=False)), 5)}
+    res["host_to_device_GB/s"] = round(mib * 2 ** 20 / (res["copy_only_ms_per_layer"] * 1e-3) / 1e9, 1)
+    return res
+
+
 def load_traffic(kernel, workload):
     """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
     the same counters on a copy kernel of known size); kept as text under profiles/."""
@@ -282,7 +321,9 @@ def main():
         "reconstruction_ms": round(per_call["rerope"] + per_call["qkv"] + per_call["scatter"] + per_call["attn"], 5),
     }
     if not args.no_tail:
-        out["next_rows"] = {"layer_tail": tail_leg(layers[0], shape, args.d_ff, dev)}
+        lens = [c.length for r in wl.requests for c in r.chunks]
+        out["next_rows"] = {"layer_tail": tail_leg(layers[0], shape, args.d_ff, dev),
+                            "layer_pipeline": pipeline_leg(layers[0], lens)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.ratio, args.cpu_sample_rows)
     print(json.dumps(out))

@@ -248,3 +248,92 @@ def extract_anchors(desc, k: torch.Tensor, v: torch.Tensor, chunk_lens: List[int
     av = torch.empty_like(ak)
     qb.qcf_gather(desc, k, v, row, total, rows, ak, av)
     return row[:total], ak[:total], av[:total]
+
+
+# ------------------------------------------------------------------ layer pipeline: chunk caches streamed from the host
+
+class ChunkStreamer:
+    """Per-layer loop in which the chunk caches of layer i+1 travel from pinned host memory to the device on a
+    copy stream while layer i is reconstructed on the compute stream (Section 3.1 Phase 4 loads and recomputes
+    "layer by layer" in a pipeline).  Two device staging buffers; the re-rotation is the only reader of a staging
+    buffer, so a buffer is free again as soon as its layer's qcf_rerope has run.
+
+    host_layers: one (k, v) pair of pinned host tensors [rows, H_kv, d] per layer, holding that layer's chunk
+    caches back to back in the order of the layer's chunk table (as `host_chunk_caches` builds them)."""
+
+    def __init__(self, L: DeviceLayer, chunk_lens: List[int], host_layers):
+        self.L = L
+        self.host = host_layers
+        dev = L.k_fused.device
+        rows = int(sum(chunk_lens))
+        hk0 = host_layers[0][0]
+        assert hk0.is_pinned() and tuple(hk0.shape[0:1]) == (rows,)
+        self.stage = [(torch.empty_like(hk0, device=dev), torch.empty_like(hk0, device=dev)) for _ in range(2)]
+        table = bytes(L.chunks_dev.cpu().numpy().tobytes())
+        n = L.n_chunks
+        self.tables = []
+        row_bytes = hk0.shape[1] * hk0.shape[2] * hk0.element_size()
+        for dk, dv in self.stage:
+            t = (qb.ChunkDesc * n).from_buffer_copy(table)
+            off = 0
+            for c in range(n):
+                t[c].k_src = dk.data_ptr() + off * row_bytes
+                t[c].v_src = dv.data_ptr() + off * row_bytes
+                off += chunk_lens[c]
+            self.tables.append(torch.frombuffer(bytearray(bytes(t)), dtype=torch.uint8).to(dev))
+        self.copy_stream = torch.cuda.Stream(device=dev)
+        self.copied = [torch.cuda.Event() for _ in range(2)]
+        self.consumed = [torch.cuda.Event() for _ in range(2)]
+
+    def _prefetch(self, layer: int, first_use: bool) -> None:
+        s = layer % 2
+        with torch.cuda.stream(self.copy_stream):
+            if not first_use:
+                self.copy_stream.wait_event(self.consumed[s])      # the stage's previous layer has been re-rotated
+            self.stage[s][0].copy_(self.host[layer][0], non_blocking=True)
+            self.stage[s][1].copy_(self.host[layer][1], non_blocking=True)
+            self.copied[s].record(self.copy_stream)
+
+    def run(self, n_layers: int, after_layer=None, overlap: bool = True) -> None:
+        """Reconstruction (rerope, qkv, scatter, attn) of n_layers layers on the current stream.  after_layer(i) is
+        called after layer i has been enqueued (e.g. to copy results out).  overlap=False waits for every copy
+        before computing and for every layer before the next copy (the serial reference)."""
+        L = self.L
+        cur = torch.cuda.current_stream()
+        self._prefetch(0, True)
+        for i in range(n_layers):
+            s = i % 2
+            cur.wait_event(self.copied[s])
+            qb.qcf_rerope(L.desc, self.tables[s], L.n_chunks, L.total_ctx, L.k_fused, L.v_fused, L.ws_rerope)
+            self.consumed[s].record(cur)
+            if overlap and i + 1 < n_layers:
+                self._prefetch(i + 1, i + 1 < 2)
+            step_qkv(L)
+            step_scatter(L)
+            step_attn(L)
+            if after_layer is not None:
+                after_layer(i)
+            if not overlap and i + 1 < n_layers:
+                cur.synchronize()
+                self._prefetch(i + 1, i + 1 < 2)
+                self.copy_stream.synchronize()
+
+
+def host_chunk_caches(L: DeviceLayer, seed: int, n_layers: int):
+    """Pinned host copies of n_layers sets of chunk caches shaped like the layer's own (layer 0 = the layer's own
+    caches, the others = seeded random values of the same shape and element type)."""
+    ks = torch.cat([k for k, _ in L.chunk_tensors])
+    vs = torch.cat([v for _, v in L.chunk_tensors])
+    out = []
+    g = torch.Generator().manual_seed(seed)
+    for i in range(n_layers):
+        hk = torch.empty(ks.shape, dtype=ks.dtype, pin_memory=True)
+        hv = torch.empty(vs.shape, dtype=vs.dtype, pin_memory=True)
+        if i == 0:
+            hk.copy_(ks)
+            hv.copy_(vs)
+        else:
+            hk.copy_(torch.randn(ks.shape, generator=g).to(ks.dtype))
+            hv.copy_(torch.randn(vs.shape, generator=g).to(vs.dtype))
+        out.append((hk, hv))
+    return out

@@ -143,3 +143,30 @@ def test_two_layer_chain_with_query_rows():
         # one element-type rounding step may differ per stage; it must not grow through the chain
         assert np.all(err <= 2e-2 + 2.0 ** -7 * np.abs(h_ref)), f"layer {l}"
         assert np.mean(err) < 2e-3
+
+
+def test_chunk_caches_streamed_from_the_host_give_the_same_layers():
+    """Layers whose chunk caches arrive over a copy stream (double-buffered) produce bit-identical results to the
+    same layers run one after the other with every copy awaited."""
+    wl = inputs.make_config(1, pipeline.HipPlantOps(DEV), scale=0.25)
+    L = pipeline.upload(wl, DEV)
+    pipeline.enqueue_layer(L)                                   # critical layer: fixes the selection
+    torch.cuda.synchronize()
+    lens = [c.length for r in wl.requests for c in r.chunks]
+    n_layers = 5
+    host = pipeline.host_chunk_caches(L, seed=3, n_layers=n_layers)
+    st = pipeline.ChunkStreamer(L, lens, host)
+    results = {}
+    for mode in (False, True):
+        outs = []
+        st.run(n_layers, after_layer=lambda i: outs.append((L.k_fused.clone(), L.o_sel.clone())), overlap=mode)
+        torch.cuda.synchronize()
+        results[mode] = outs
+    for i in range(n_layers):
+        assert torch.equal(results[True][i][0], results[False][i][0]), f"fused K, layer {i}"
+        assert torch.equal(results[True][i][1], results[False][i][1]), f"O rows, layer {i}"
+    # layer 0 streams the layer's own caches: the same result as the resident path
+    pipeline.enqueue_layer(L, critical=False)
+    torch.cuda.synchronize()
+    assert torch.equal(results[True][0][1], L.o_sel)
+    assert not torch.equal(results[True][1][1], results[True][0][1])     # other layers really hold other caches
