@@ -207,3 +207,63 @@ def test_config3_full_size_sampled_rows():
     err = assert_close(to_np(out["o_sel"])[rows], o_ref, sh.dtype, "O rows")
     assert max_abs(to_np(out["lse"])[rows], lse_ref) < 5e-2
     say(f"  cfg3: sampled O max abs err {err:.4f}")
+
+
+def test_config4_full_size_ragged_batch_sampled():
+    """Ragged batch of 16 requests sharing chunk caches at different offsets (about 147k context tokens):
+    streaming, scoring and selection of every request in full; patched K/V of three requests and attention
+    of a few rows of each of them against the oracle."""
+    wl = inputs.make_config(4, orc.PlantOps())
+    sh = wl.shape
+    H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    qz = quantizer(sh.dtype)
+    B = len(wl.requests)
+    say(f"  cfg4: {B} requests, {sum(r.T for r in wl.requests)} context tokens: upload + GPU layer")
+    L = pipeline.upload(wl, DEV, shared_chunks={})
+    out = pipeline.fuse_layer(L)
+    torch.cuda.synchronize()
+    ctx_off = np.concatenate([[0], np.cumsum(L.ctx_lens)])
+    sel_off = np.concatenate([[0], np.cumsum(L.sel_counts)])
+    score = to_np(out["score"])
+    idx_gpu = out["sel_idx"].cpu().numpy()
+    fused, ref_idx, n_diff = [], [], 0
+    for b, req in enumerate(wl.requests):
+        kf, vf = orc.rerope([c.k for c in req.chunks], [c.v for c in req.chunks], req.dst_pos0, sh.rope_base)
+        kf, vf = qz(kf), qz(vf)
+        s_ref = orc.score(req.q_probe, kf)
+        n = orc.select_count(req.T, wl.ratio)
+        assert n == L.sel_counts[b]
+        g = score[ctx_off[b]:ctx_off[b + 1]]
+        assert np.all(np.abs(g - s_ref) <= SCORE_REL * s_ref + 1e-12), f"score, request {b}"
+        n_diff += assert_indices_match(idx_gpu[sel_off[b]:sel_off[b + 1]], s_ref, n, f"request {b}")
+        fused.append((kf, vf))
+        ref_idx.append(orc.select(s_ref, n))
+    say(f"  cfg4: scores and indices of all requests agree ({n_diff} indices inside the threshold band)")
+    if n_diff:
+        flat = np.concatenate(ref_idx).astype(np.int32)
+        rowsf = np.concatenate([r + ctx_off[b] for b, r in enumerate(ref_idx)]).astype(np.int32)
+        L.sel_idx[:len(flat)] = torch.from_numpy(flat).to(DEV)
+        L.sel_row[:len(flat)] = torch.from_numpy(rowsf).to(DEV)
+        L.sel_pos[:len(flat)] = torch.from_numpy(flat).to(DEV)
+        pipeline.step_rerope(L); pipeline.step_qkv(L); pipeline.step_scatter(L); pipeline.step_attn(L)
+        torch.cuda.synchronize()
+    w = wl.w_qkv.astype(np.float64)
+    k_all, v_all = to_np(out["k_fused"]), to_np(out["v_fused"])
+    q_all, o_all = to_np(out["q_sel"]), to_np(out["o_sel"])
+    lens = [r.T for r in wl.requests]
+    for b in sorted({0, int(np.argmin(lens)), int(np.argmax(lens))}):
+        req, idx, n = wl.requests[b], ref_idx[b], len(ref_idx[b])
+        kf, vf = fused[b]
+        y_kv = req.x_ctx[idx].astype(np.float64) @ w[H * D:].T
+        k_new = qz(orc.rope_at(y_kv[:, :Hkv * D].reshape(n, Hkv, D), idx, sh.rope_base))
+        v_new = qz(y_kv[:, Hkv * D:].reshape(n, Hkv, D))
+        kp, vp = orc.scatter(kf, vf, k_new, v_new, idx)
+        assert_close(k_all[ctx_off[b]:ctx_off[b + 1]], kp, sh.dtype, f"patched K, request {b}")
+        assert_close(v_all[ctx_off[b]:ctx_off[b + 1]], vp, sh.dtype, f"patched V, request {b}")
+        rows = np.unique(np.concatenate([[0, n - 1], np.random.default_rng(b).choice(n, size=6, replace=False)]))
+        q_s, _, _ = orc.recompute_qkv(req.x_ctx[idx[rows]], wl.w_qkv, idx[rows], H, Hkv, D, sh.rope_base)
+        q_s = qz(q_s)
+        assert_close(q_all[sel_off[b] + rows], q_s, sh.dtype, f"Q rows, request {b}")
+        o_ref, _ = orc.recompute_attn(q_s, idx[rows], kp, vp)
+        err = assert_close(o_all[sel_off[b] + rows], o_ref, sh.dtype, f"O rows, request {b}")
+        say(f"  cfg4: request {b} (T={req.T}): sampled O max abs err {err:.4f}")
