@@ -3,8 +3,8 @@
 // attention the context token j receives.
 //
 // bf16 / head_dim 128 path (the dense contraction runs on MFMA):
-//   pass 1  per (64-token slice, KV head): logits of all probe rows of the group against the
-//           slice -> per-row (max, sum-exp) partials, in the log2 domain;
+//   pass 1  per (64-token slice, KV head, block of 128 group rows): logits of the block's probe rows
+//           against the slice -> per-row (max, sum-exp) partials, in the log2 domain;
 //   combine per (probe row, head): log2-sum-exp over the request's slices;
 //   pass 2  logits again, p = exp2(logit - lse), summed over the rows of the group ->
 //           per-KV-head column sums;
@@ -102,6 +102,9 @@ constexpr int kTokPerWave = 64;                 // tokens a wave keeps stationar
 constexpr int kWavesPerWg = 4;
 constexpr int kTokPerWg = kTokPerWave * kWavesPerWg;
 constexpr int kRowBlock = 320;                  // probe rows (of one group) staged in LDS at a time
+constexpr int kRowSplit1 = 128;                 // pass 1 only: group rows per workgroup (grid.z); its partials are
+                                                // per row, so splitting the rows costs nothing downstream and puts
+                                                // several workgroups on a compute unit
 constexpr int kQStride = 128;                   // bf16 elements per staged row (swizzled, no padding)
 
 struct ScoreArgs {
@@ -195,8 +198,10 @@ __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
   load_k_frags(a, c0, T, tok0, g, lane, kf);
   float2* part = a.part + (int64_t)(slice0 + wave) * (a.total_probe * a.H);
 
-  for (int r_begin = 0; r_begin < rows; r_begin += kRowBlock) {
-    const int n_rows = min(kRowBlock, rows - r_begin);
+  const int r_lo = (int)blockIdx.z * kRowSplit1;
+  const int r_hi = min(rows, r_lo + kRowSplit1);
+  for (int r_begin = r_lo; r_begin < r_hi; r_begin += kRowSplit1) {
+    const int n_rows = r_hi - r_begin;
     const int n_pad = (n_rows + 31) & ~31;
     __syncthreads();
     stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
@@ -420,8 +425,8 @@ MfmaWs mfma_ws(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t 
   return w;
 }
 
-constexpr size_t kPass1Lds = (size_t)kRowBlock * kQStride * 2;
-constexpr size_t kPass2Lds = kPass1Lds + (size_t)kRowBlock * 8;
+constexpr size_t kPass1Lds = (size_t)kRowSplit1 * kQStride * 2;
+constexpr size_t kPass2Lds = (size_t)kRowBlock * kQStride * 2 + (size_t)kRowBlock * 8;
 
 }  // namespace
 
@@ -494,8 +499,11 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
     attr_done = true;
   }
   if (total_probe > 0) {
-    if (probe_limit) score_pass1<true><<<grid, block, kPass1Lds, st>>>(a);
-    else score_pass1<false><<<grid, block, kPass1Lds, st>>>(a);
+    const int64_t row_splits = (total_probe * a.G + kRowSplit1 - 1) / kRowSplit1;      // upper bound over the requests
+    if (row_splits > 65535) return fail(QCF_ERR_UNSUPPORTED, "score: too many probe rows");
+    const dim3 grid1((unsigned)n_tiles, (unsigned)Hkv, (unsigned)row_splits);
+    if (probe_limit) score_pass1<true><<<grid1, block, kPass1Lds, st>>>(a);
+    else score_pass1<false><<<grid1, block, kPass1Lds, st>>>(a);
     QCF_TRY_LAUNCH("score pass 1");
     score_combine<<<dim3((unsigned)((total_probe * H + 15) / 16)), dim3(256), 0, st>>>(a);
     QCF_TRY_LAUNCH("score combine");
