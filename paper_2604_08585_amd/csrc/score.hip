@@ -270,11 +270,22 @@ __global__ __launch_bounds__(256) void score_combine(ScoreArgs a) {
         if (bb < b) slice0 += ((T + kTokPerWg - 1) / kTokPerWg) * kWavesPerWg;
       }
       const int n_slices = (T + kTokPerWave - 1) / kTokPerWave;
-      for (int s = sg; s < n_slices; s += 16) {
-        const float2 p = a.part[(int64_t)(slice0 + s) * total + idx];
-        if (p.x > -INFINITY) {
-          const float mn = fmaxf(m, p.x);
-          z = z * exp2f(m - mn) + p.y * exp2f(p.x - mn);
+      // eight slices at a time: all loads first, then one maximum and one rescaled sum
+      for (int s0 = sg; s0 < n_slices; s0 += 16 * 8) {
+        float2 p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int s = s0 + 16 * u;
+          p[u] = (s < n_slices) ? a.part[(int64_t)(slice0 + s) * total + idx] : make_float2(-INFINITY, 0.f);
+        }
+        float mn = m;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mn = fmaxf(mn, p[u].x);
+        if (mn > -INFINITY) {
+          z *= exp2f(m - mn);
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (p[u].x > -INFINITY) z += p[u].y * exp2f(p[u].x - mn);
           m = mn;
         }
       }
