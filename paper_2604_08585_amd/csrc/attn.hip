@@ -52,6 +52,7 @@ struct AttnArgs {
   bf16_t* part_o;        // [unit][128 rows][128] normalised partial outputs of split row blocks
   float* part_lse;       // [unit][128 rows] log2-domain log-sum-exp of each partial (-inf: no visible key)
   int32_t* units;        // units[0] = number of work units, then (row block << 8 | segment), longest first
+  int32_t* blk_tiles;    // [row block] key tiles of the block, written by the plan kernel for the merge kernel
 };
 
 // ------------------------------------------------------------------ generic path
@@ -441,6 +442,7 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(AttnArgs a) {
   for (int pass = 0; pass < 2; ++pass) {
     for (int blk = tid; blk < a.n_row_blocks; blk += 1024) {
       const int n_tiles = (s_vis[blk] + kBKV - 1) / kBKV;
+      if (pass == 0) a.blk_tiles[blk] = n_tiles;
       const int n_seg = max(1, (n_tiles + a.seg_tiles - 1) / a.seg_tiles);   // a block without tiles still writes zeros
       for (int sg = 0; sg < n_seg; ++sg) {
         const int len = min(a.seg_tiles, n_tiles - sg * a.seg_tiles);
@@ -465,13 +467,14 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(AttnArgs a) {
 // thread per 8 output elements.  out = sum_s w_s O_s with w_s = 2^(lse_s - lse), lse = log2 sum_s 2^lse_s.
 constexpr int kMergeWgs = kRowsPerWg * 16 / 256;
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
-  __shared__ int s_vis[kRowsPerWg];
   const int tid = threadIdx.x;
   const int BR = kRowsPerWg / a.G;
   const int part = (int)(blockIdx.x % kMergeWgs);
   const int bh = (int)(blockIdx.x / kMergeWgs);
   const int g = bh % a.Hkv;
   const int blk = bh / a.Hkv;
+  const int n_tiles = a.blk_tiles[blk];
+  if (n_tiles <= a.seg_tiles) return;               // not split: the main kernel wrote the result
   int wg = blk, b = 0;
   int64_t s0 = 0, s1 = 0;
   for (; b < a.B; ++b) {
@@ -482,19 +485,6 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     wg -= nb;
   }
   if (b >= a.B) return;
-  const int64_t c0 = min(max(a.ctx_off[b], (int64_t)0), a.total_ctx);
-  const int64_t c1 = min(max(a.ctx_off[b + 1], c0), a.total_ctx);
-  const int T = (int)(c1 - c0);
-  const int64_t p0 = a.ctx_pos0 ? a.ctx_pos0[b] : 0;
-  if (tid < BR) {
-    const int64_t sr = s0 + (int64_t)wg * BR + tid;
-    s_vis[tid] = sr < s1 ? (int)min((int64_t)T, max((int64_t)0, (int64_t)a.sel_pos[sr] - p0 + 1)) : 0;
-  }
-  __syncthreads();
-  int vis_max = 0;
-  for (int i = 0; i < BR; ++i) vis_max = max(vis_max, s_vis[i]);
-  const int n_tiles = (vis_max + kBKV - 1) / kBKV;
-  if (n_tiles <= a.seg_tiles) return;               // not split: the main kernel wrote the result
   const int n_seg = (n_tiles + a.seg_tiles - 1) / a.seg_tiles;
   const int r = part * 16 + (tid >> 4), ch = tid & 15;          // row of the block, 8-element chunk
   const int64_t srow = s0 + (int64_t)wg * BR + r / a.G;
@@ -504,20 +494,36 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
   const int64_t slot0 = ((int64_t)blk * a.Hkv + g) * a.n_seg_max;
   const float* pl = a.part_lse + slot0 * kRowsPerWg + r;
   const bf16_t* po = a.part_o + (slot0 * kRowsPerWg + r) * 128 + 8 * ch;
-  float mx = -INFINITY;
-#pragma unroll 4
-  for (int sg = 0; sg < n_seg; ++sg) mx = fmaxf(mx, pl[(int64_t)sg * kRowsPerWg]);
+  // four segments at a time: every load first, then the running maximum, the weights and the weighted sum
+  float mx = -INFINITY, wsum = 0.f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float wsum = 0.f;
-  if (mx > -INFINITY) {
-#pragma unroll 4
-    for (int sg = 0; sg < n_seg; ++sg) {
-      const float w = __builtin_amdgcn_exp2f(pl[(int64_t)sg * kRowsPerWg] - mx);
-      float f[8];
-      Vec16<bf16_t>::unpack(*reinterpret_cast<const u32x4*>(po + (int64_t)sg * kRowsPerWg * 128), f);
-      wsum += w;
+  for (int sg0 = 0; sg0 < n_seg; sg0 += 4) {
+    float l[4];
+    u32x4 raw[4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] += w * f[e];
+    for (int u = 0; u < 4; ++u) {
+      const bool ok = sg0 + u < n_seg;
+      l[u] = ok ? pl[(int64_t)(sg0 + u) * kRowsPerWg] : -INFINITY;
+      raw[u] = ok ? *reinterpret_cast<const u32x4*>(po + (int64_t)(sg0 + u) * kRowsPerWg * 128) : u32x4{0u, 0u, 0u, 0u};
+    }
+    float mn = mx;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) mn = fmaxf(mn, l[u]);
+    if (mn > -INFINITY) {
+      const float resc = __builtin_amdgcn_exp2f(mx - mn);        // 0 while nothing was visible so far
+      wsum *= resc;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] *= resc;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float w = __builtin_amdgcn_exp2f(l[u] - mn);        // 0 for a segment that saw nothing
+        float f[8];
+        Vec16<bf16_t>::unpack(raw[u], f);
+        wsum += w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += w * f[e];
+      }
+      mx = mn;
     }
   }
   const float inv = wsum > 0.f ? 1.f / wsum : 0.f;
@@ -559,6 +565,7 @@ size_t part_lse_bytes(int64_t n_blocks, int n_seg_max) {
 size_t units_bytes(int64_t n_row_blocks, int n_seg_max) {
   return align_up((size_t)(n_row_blocks * n_seg_max + 1) * sizeof(int32_t), 256);
 }
+size_t blk_tiles_bytes(int64_t n_row_blocks) { return align_up((size_t)n_row_blocks * sizeof(int32_t), 256); }
 
 bool use_mfma(const qcf_layer_desc& L) {
   const int G = L.n_q_heads / L.n_kv_heads;
@@ -574,7 +581,7 @@ size_t attn_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_sel, int
   const Split sp = choose_split(n_blocks, total_ctx);
   if (sp.n_seg_max <= 1) return 0;
   return part_o_bytes(n_blocks, sp.n_seg_max) + part_lse_bytes(n_blocks, sp.n_seg_max) +
-         units_bytes(n_blocks / L.n_kv_heads, sp.n_seg_max);
+         units_bytes(n_blocks / L.n_kv_heads, sp.n_seg_max) + blk_tiles_bytes(n_blocks / L.n_kv_heads);
 }
 
 qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const int32_t* sel_pos,
@@ -588,7 +595,7 @@ qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const 
   a.B = B; a.H = L.n_q_heads; a.Hkv = L.n_kv_heads; a.G = L.n_q_heads / L.n_kv_heads; a.D = L.head_dim;
   a.o = o; a.lse = lse;
   a.n_row_blocks = 0;
-  a.seg_tiles = 0x3fffffff; a.n_seg_max = 1; a.part_o = nullptr; a.part_lse = nullptr; a.units = nullptr;
+  a.seg_tiles = 0x3fffffff; a.n_seg_max = 1; a.part_o = nullptr; a.part_lse = nullptr; a.units = nullptr; a.blk_tiles = nullptr;
   if (use_mfma(L)) {
     const int BR = kRowsPerWg / a.G;
     const int64_t nb = (total_sel + BR - 1) / BR + B;
@@ -604,6 +611,7 @@ qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const 
       a.part_lse = reinterpret_cast<float*>(w + part_o_bytes(nb * a.Hkv, sp.n_seg_max));
       a.units = reinterpret_cast<int32_t*>(w + part_o_bytes(nb * a.Hkv, sp.n_seg_max) +
                                            part_lse_bytes(nb * a.Hkv, sp.n_seg_max));
+      a.blk_tiles = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(a.units) + units_bytes(nb, sp.n_seg_max));
     }
     static bool attr_done = false;
     if (!attr_done) {
