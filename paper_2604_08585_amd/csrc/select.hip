@@ -36,7 +36,6 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     const float* __restrict__ score, const int64_t* __restrict__ ctx_off, int64_t total_ctx,
     const int64_t* __restrict__ sel_off, int64_t total_sel, const int32_t* __restrict__ ctx_pos0,
     int32_t* __restrict__ sel_idx, int32_t* __restrict__ sel_row, int32_t* __restrict__ sel_pos) {
-  __shared__ uint32_t hist[kWaves][256];
   __shared__ uint32_t merged[256];
   __shared__ uint64_t wave_tot[kWaves];
   __shared__ uint32_t red_lo[kWaves], red_hi[kWaves];
@@ -89,6 +88,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
       hi = max(hi, (uint32_t)__shfl_xor((int)hi, d, 64));
     }
     if (lane == 0) { red_lo[wave] = lo; red_hi[wave] = hi; }
+    if (tid < 256) merged[tid] = 0u;
     __syncthreads();
     lo = red_lo[0]; hi = red_hi[0];
 #pragma unroll
@@ -101,26 +101,18 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
       const int w = min(8, bits);
       const int shift = bits - w;
       const uint32_t mask = (1u << w) - 1u;
-      for (int i = tid; i < kWaves * 256; i += kThreads) (&hist[0][0])[i] = 0u;
-      __syncthreads();
+      // (merged[] was cleared before the loop and is cleared again by wave 0 after each pass)
       QCF_FOR_KEYS(i, {
         const uint32_t key = QCF_KEY(i);
         const uint32_t high = (bits >= 32) ? 0u : (key >> bits);
-        if (high == prefix) atomicAdd(&hist[wave][(key >> shift) & mask], 1u);
+        if (high == prefix) atomicAdd(&merged[(key >> shift) & mask], 1u);
       })
-      __syncthreads();
-      if (tid < 256) {
-        uint32_t acc = 0;
-#pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) acc += hist[ww][tid];
-        merged[tid] = acc;
-      }
       __syncthreads();
       if (wave == 0) {
         uint32_t c[4];
         uint32_t tot = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { c[q] = merged[4 * lane + q]; tot += c[q]; }
+        for (int q = 0; q < 4; ++q) { c[q] = merged[4 * lane + q]; tot += c[q]; merged[4 * lane + q] = 0u; }
         uint32_t suffix = tot;               // sum over lanes >= this one
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -138,7 +130,6 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
       prefix = (prefix << w) | s_digit;
       k = s_k;
       bits = shift;
-      __syncthreads();
     }
     tau = prefix;
   }
