@@ -128,6 +128,7 @@ constexpr int kVTile = kBKV * 128;
 constexpr int kStage = kKTile + kVTile;
 constexpr size_t kAttnLds = (size_t)2 * kStage * 2;
 constexpr int kRowsPerWg = 128;             // (selected row, head-in-group) pairs per workgroup
+constexpr float kLazyRescale = 8.f;         // log2 units the running maximum may lag behind the true one
 
 // LDS transposing read: within each group of 16 lanes, lane i receives element i%4 of the four
 // 8-byte rows addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4 of the group.
@@ -317,9 +318,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int v = 1; v < 32; ++v) mx = fmaxf(mx, p[v]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * k2);
+    // The reference point of the exponentials only moves when the maximum grows by more than 2^8: until
+    // then probabilities up to 256 are accumulated against the old one (the final division by the
+    // denominator makes the result independent of the reference point), and the running output is
+    // rescaled far less often.
+    const float m_cand = fmaxf(m_run, mx * k2);
+    const bool bump = m_cand > m_run + kLazyRescale;          // also the first visible tile (m_run = -inf)
+    const float m_new = bump ? m_cand : m_run;
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+    const float alpha = bump ? __builtin_amdgcn_exp2f(m_run - m_use) : 1.f;
     float sum = 0.f;
 #pragma unroll
     for (int v = 0; v < 32; ++v) {
