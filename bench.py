@@ -211,8 +211,8 @@ def load_traffic(kernel, workload):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the path is single-GPU by "
-              "design: see DESIGN.md for how it would shard)", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (requests and KV heads are the "
+              "independent axes along which the path would shard)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
