@@ -24,6 +24,17 @@ qcf_status check_hip(hipError_t e, const char* what) {
 
 qcf_status check_launch(const char* what) { return check_hip(hipGetLastError(), what); }
 
+qcf_status allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  QCF_TRY(check_hip(hipGetDevice(&dev), "hipGetDevice"));
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return QCF_OK;
+  QCF_TRY(check_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes),
+                    "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"));
+  done.fetch_or(bit, std::memory_order_release);
+  return QCF_OK;
+}
+
 static qcf_status check_desc(const qcf_layer_desc* d) {
   if (!d) return fail(QCF_ERR_INVALID_ARG, "layer descriptor is NULL");
   if (d->dtype != QCF_DTYPE_F32 && d->dtype != QCF_DTYPE_BF16)

@@ -620,12 +620,8 @@ qcf_status launch_attn(const qcf_layer_desc& L, int32_t B, const void* q, const 
                                            part_lse_bytes(nb * a.Hkv, sp.n_seg_max));
       a.blk_tiles = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(a.units) + units_bytes(nb, sp.n_seg_max));
     }
-    static bool attr_done = false;
-    if (!attr_done) {
-      QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds), "attn attr"));
-      attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&attn_mfma_kernel), kAttnLds, lds_ok));
     if (sp.n_seg_max > 1) {
       attn_plan_kernel<<<dim3(1), dim3(1024), 0, st>>>(a);
       QCF_TRY_LAUNCH("attn plan");

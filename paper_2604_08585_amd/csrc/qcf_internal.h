@@ -6,6 +6,7 @@
 #include <stddef.h>
 #include <algorithm>
 #include <cmath>
+#include <atomic>
 
 #include "qcf.h"
 
@@ -24,6 +25,10 @@ qcf_status check_launch(const char* what);
 #define QCF_TRY_LAUNCH(what) QCF_TRY(::qcf::check_launch(what))
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Raises a kernel's dynamic-LDS limit, once per device and kernel (`done` is a bit mask over device ids kept by
+// the caller, one per kernel; a repeated call from another thread is harmless).
+qcf_status allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done);
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int elem_size(int dtype) { return dtype == QCF_DTYPE_BF16 ? 2 : 4; }
 

@@ -684,14 +684,9 @@ qcf_status run_mfma(const qcf_layer_desc& L, const QkvArgs& a_in, hipStream_t st
   QkvArgs a = a_in;
   a.m_tiles = (int)mt;
   a.n_tiles = nt;
-  static bool attr_done = false;
-  if (!attr_done) {
-    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&qkv_mfma_kernel<TM, TN, WGM, WGN, 0>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS), "qkv attr"));
-    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&qkv_mfma_kernel<TM, TN, WGM, WGN, 1>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS), "qkv attr"));
-    attr_done = true;
-  }
+  static std::atomic<uint64_t> lds_ok[2];
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&qkv_mfma_kernel<TM, TN, WGM, WGN, 0>), C::LDS, lds_ok[0]));
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&qkv_mfma_kernel<TM, TN, WGM, WGN, 1>), C::LDS, lds_ok[1]));
   if (L.rope_style == 0) qkv_mfma_kernel<TM, TN, WGM, WGN, 0><<<grid, block, C::LDS, st>>>(a);
   else qkv_mfma_kernel<TM, TN, WGM, WGN, 1><<<grid, block, C::LDS, st>>>(a);
   return check_launch("qkv gemm");
@@ -707,14 +702,9 @@ qcf_status run_ws(const qcf_layer_desc& L, const QkvArgs& a_in, hipStream_t st) 
   QkvArgs a = a_in;
   a.m_tiles = (int)mt;
   a.n_tiles = nt;
-  static bool attr_done = false;
-  if (!attr_done) {
-    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&qkv_ws_kernel<0>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS), "qkv attr"));
-    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&qkv_ws_kernel<1>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS), "qkv attr"));
-    attr_done = true;
-  }
+  static std::atomic<uint64_t> lds_ok[2];
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&qkv_ws_kernel<0>), C::LDS, lds_ok[0]));
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&qkv_ws_kernel<1>), C::LDS, lds_ok[1]));
   if (L.rope_style == 0) qkv_ws_kernel<0><<<grid, block, C::LDS, st>>>(a);
   else qkv_ws_kernel<1><<<grid, block, C::LDS, st>>>(a);
   return check_launch("qkv gemm");

@@ -497,18 +497,11 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
   const dim3 grid((unsigned)n_tiles, (unsigned)Hkv), block(256);
   const int64_t red_blocks = (total_ctx + 255) / 256;
 
-  static bool attr_done = false;
-  if (!attr_done) {
-    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass1<false>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPass1Lds), "score attr"));
-    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass1<true>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPass1Lds), "score attr"));
-    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass2<false>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPass2Lds), "score attr"));
-    QCF_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass2<true>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPass2Lds), "score attr"));
-    attr_done = true;
-  }
+  static std::atomic<uint64_t> lds_ok[4];
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&score_pass1<false>), kPass1Lds, lds_ok[0]));
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&score_pass1<true>), kPass1Lds, lds_ok[1]));
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&score_pass2<false>), kPass2Lds, lds_ok[2]));
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&score_pass2<true>), kPass2Lds, lds_ok[3]));
   if (total_probe > 0) {
     const int64_t row_splits = (total_probe * a.G + kRowSplit1 - 1) / kRowSplit1;      // upper bound over the requests
     if (row_splits > 65535) return fail(QCF_ERR_UNSUPPORTED, "score: too many probe rows");
