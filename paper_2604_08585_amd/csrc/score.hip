@@ -3,11 +3,12 @@
 // attention the context token j receives.
 //
 // bf16 / head_dim 128 path (the dense contraction runs on MFMA):
-//   pass 1  per (64-token slice, KV head, block of 128 group rows): logits of the block's probe rows
-//           against the slice -> per-row (max, sum-exp) partials, in the log2 domain;
-//   combine per (probe row, head): log2-sum-exp over the request's slices;
-//   pass 2  logits again, p = exp2(logit - lse), summed over the rows of the group ->
-//           per-KV-head column sums;
+//   pass 1  per (256-token tile, KV head, block of 128 group rows): logits of the block's probe rows
+//           against the tile (a wave keeps 64 tokens) -> per-row (max, sum-exp) partials of the tile,
+//           in the log2 domain;
+//   pass 2  every workgroup first folds the partials of its group's rows over the request's tiles into
+//           a log2-sum-exp per row (in a fixed order, so all workgroups get the same value); logits
+//           again, p = exp2(logit - lse), summed over the rows of the group -> per-KV-head column sums;
 //   reduce  fixed-order sum over KV heads, times 1/(R*H).
 // No floating-point atomics anywhere, so scores (and the indices selected from them) are
 // bit-stable from run to run.
@@ -115,18 +116,17 @@ struct ScoreArgs {
   const int32_t* probe_limit;
   int64_t total_probe, total_ctx;
   int B, H, Hkv, G;
-  float2* part;               // [n_slices][total_probe * H] (max2, sumexp2) per 64-token slice
-  float* lse2;                // [total_probe * H] log2-sum-exp of the scaled logits
+  float2* part;               // [n_tiles][total_probe * H] (max2, sumexp2) per 256-token tile
   float* colsum;              // [Hkv][total_ctx]
   float* score;
-  int n_slices;               // upper bound on 64-token slices over all requests
 };
 
-// Maps a workgroup index to (request, first token of its 256-token tile).  Tiles are aligned to
-// the start of each request.  Returns false when the index is past the last tile.
+// Maps a workgroup index (= tile number over all requests) to (request, first token of its 256-token
+// tile, number of the request's first tile).  Tiles are aligned to the start of each request.  Returns
+// false when the index is past the last tile.
 __device__ __forceinline__ bool locate_tile(const ScoreArgs& a, int wg, int& b, int64_t& c0, int& T,
-                                            int& tile_tok0, int& slice0) {
-  int slices_before = 0;
+                                            int& tile_tok0, int& tile_first) {
+  tile_first = 0;
   for (b = 0; b < a.B; ++b) {
     c0 = min(max(a.ctx_off[b], (int64_t)0), a.total_ctx);
     const int64_t c1 = min(max(a.ctx_off[b + 1], c0), a.total_ctx);
@@ -134,11 +134,10 @@ __device__ __forceinline__ bool locate_tile(const ScoreArgs& a, int wg, int& b, 
     const int nt = (T + kTokPerWg - 1) / kTokPerWg;
     if (wg < nt) {
       tile_tok0 = wg * kTokPerWg;
-      slice0 = slices_before + wg * kWavesPerWg;
       return true;
     }
     wg -= nt;
-    slices_before += nt * kWavesPerWg;
+    tile_first += nt;
   }
   return false;
 }
@@ -180,14 +179,19 @@ __device__ __forceinline__ void stage_q_async(const ScoreArgs& a, int64_t p0, in
 template <bool LIMIT>
 __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
+  float2* sPart = reinterpret_cast<float2*>(smem + (size_t)kRowSplit1 * kQStride * 2);   // [4 waves][kRowSplit1]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = blockIdx.y;
-  int b, T, tile_tok0, slice0;
+  int b, T, tile_tok0, tile_first;
   int64_t c0;
-  if (!locate_tile(a, blockIdx.x, b, c0, T, tile_tok0, slice0)) return;
+  if (!locate_tile(a, blockIdx.x, b, c0, T, tile_tok0, tile_first)) return;
   const int64_t p0 = min(max(a.probe_off[b], (int64_t)0), a.total_probe);
   const int64_t p1 = min(max(a.probe_off[b + 1], p0), a.total_probe);
   const int rows = (int)(p1 - p0) * a.G;         // probe rows x heads of the group
+  const int r_begin = (int)blockIdx.z * kRowSplit1;
+  if (r_begin >= rows) return;
+  const int n_rows = min(rows - r_begin, kRowSplit1);
+  const int n_pad = (n_rows + 31) & ~31;
   const int tok0 = tile_tok0 + wave * kTokPerWave;
   const bool wave_active = tok0 < T;
   const float k2 = kLog2e * 0.08838834764831845f;   // log2(e) / sqrt(128)
@@ -196,19 +200,12 @@ __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
 
   bf16x8 kf[2][8];
   load_k_frags(a, c0, T, tok0, g, lane, kf);
-  float2* part = a.part + (int64_t)(slice0 + wave) * (a.total_probe * a.H);
-
-  const int r_lo = (int)blockIdx.z * kRowSplit1;
-  const int r_hi = min(rows, r_lo + kRowSplit1);
-  for (int r_begin = r_lo; r_begin < r_hi; r_begin += kRowSplit1) {
-    const int n_rows = r_hi - r_begin;
-    const int n_pad = (n_rows + 31) & ~31;
-    __syncthreads();
-    stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (!wave_active) continue;
-    for (int rt = 0; rt < n_pad; rt += 32) {
+  stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  for (int rt = 0; rt < n_pad; rt += 32) {
+    float mx = -INFINITY, sum = 0.f;
+    if (wave_active) {
       floatx16 acc0 = {0}, acc1 = {0};
       const unsigned char* qrow = smem + rt * 256;
 #pragma unroll
@@ -232,80 +229,47 @@ __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
           s[v] = (t0 < lim) ? s[v] : -INFINITY;
         }
       }
-      float mx = s[0];
+      mx = s[0];
 #pragma unroll
       for (int v = 1; v < 32; ++v) mx = fmaxf(mx, s[v]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * k2;          // k2 > 0: scaling commutes with the maximum
       const float m_use = (mx == -INFINITY) ? 0.f : mx;
-      float sum = 0.f;
 #pragma unroll
       for (int v = 0; v < 32; ++v) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], k2, -m_use));
       sum += __shfl_xor(sum, 32, 64);
-      if (lane < 32 && r < rows) {
-        const int i = r / a.G, hh = r - i * a.G;
-        part[(p0 + i) * a.H + g * a.G + hh] = make_float2(mx, sum);
-      }
     }
+    if (lane < 32) sPart[wave * kRowSplit1 + rt + lane] = make_float2(mx, sum);
+  }
+  __syncthreads();
+  // the four waves' 64-token partials of a row fold, in wave order, into the tile's partial
+  float2* part = a.part + (int64_t)blockIdx.x * (a.total_probe * a.H);
+  for (int r = tid; r < n_rows; r += 256) {
+    float2 p[kWavesPerWg];
+    float m = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWavesPerWg; ++w) { p[w] = sPart[w * kRowSplit1 + r]; m = fmaxf(m, p[w].x); }
+    float z = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerWg; ++w)
+      if (p[w].x > -INFINITY) z += p[w].y * exp2f(p[w].x - m);
+    const int rr = r_begin + r;
+    const int i = rr / a.G, hh = rr - i * a.G;
+    part[(p0 + i) * a.H + g * a.G + hh] = make_float2(m, z);
   }
 }
 
-// log2-sum-exp over the request's slices for every (probe row, head): a workgroup handles 16
-// (row, head) pairs; 16 threads per pair fold every 16th slice, then one thread folds the 16
-// partial results in a fixed order (deterministic).
-__global__ __launch_bounds__(256) void score_combine(ScoreArgs a) {
-  __shared__ float sm[16][17], sz[16][17];
-  const int il = threadIdx.x & 15, sg = threadIdx.x >> 4;
-  const int64_t total = a.total_probe * a.H;
-  const int64_t idx = (int64_t)blockIdx.x * 16 + il;
-  float m = -INFINITY, z = 0.f;
-  if (idx < total) {
-    const int64_t row = idx / a.H;
-    const int b = find_request(a.probe_off, a.B, row);
-    if (b < a.B) {
-      int slice0 = 0, T = 0;
-      for (int bb = 0; bb <= b; ++bb) {
-        const int64_t c0 = min(max(a.ctx_off[bb], (int64_t)0), a.total_ctx);
-        const int64_t c1 = min(max(a.ctx_off[bb + 1], c0), a.total_ctx);
-        T = (int)(c1 - c0);
-        if (bb < b) slice0 += ((T + kTokPerWg - 1) / kTokPerWg) * kWavesPerWg;
-      }
-      const int n_slices = (T + kTokPerWave - 1) / kTokPerWave;
-      // eight slices at a time: all loads first, then one maximum and one rescaled sum
-      for (int s0 = sg; s0 < n_slices; s0 += 16 * 8) {
-        float2 p[8];
+// Folds a batch of (max2, sumexp2) partials, in order, into the running pair (m, z).  A partial that saw
+// nothing is (-inf, 0) and contributes 0 * exp2(-inf) = 0.
+constexpr int kFoldBatch = 32;
+__device__ __forceinline__ void fold_partials(const float2 (&p)[kFoldBatch], float& m, float& z) {
+  float mn = m;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int s = s0 + 16 * u;
-          p[u] = (s < n_slices) ? a.part[(int64_t)(slice0 + s) * total + idx] : make_float2(-INFINITY, 0.f);
-        }
-        float mn = m;
+  for (int u = 0; u < kFoldBatch; ++u) mn = fmaxf(mn, p[u].x);
+  if (mn > -INFINITY) {
+    z *= __builtin_amdgcn_exp2f(m - mn);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) mn = fmaxf(mn, p[u].x);
-        if (mn > -INFINITY) {
-          z *= exp2f(m - mn);
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
-            if (p[u].x > -INFINITY) z += p[u].y * exp2f(p[u].x - mn);
-          m = mn;
-        }
-      }
-    }
-  }
-  sm[il][sg] = m;
-  sz[il][sg] = z;
-  __syncthreads();
-  if (sg == 0 && idx < total) {
-    float mm = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) mm = fmaxf(mm, sm[il][j]);
-    float zz = 0.f;
-    if (mm > -INFINITY) {
-#pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (sm[il][j] > -INFINITY) zz += sz[il][j] * exp2f(sm[il][j] - mm);
-    }
-    // rows that see nothing get +inf so that exp2(logit - lse) is 0
-    a.lse2[idx] = (zz > 0.f) ? mm + log2f(zz) : INFINITY;
+    for (int u = 0; u < kFoldBatch; ++u) z = __builtin_fmaf(p[u].y, __builtin_amdgcn_exp2f(p[u].x - mn), z);
+    m = mn;
   }
 }
 
@@ -316,12 +280,14 @@ __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
   int* sLim = reinterpret_cast<int*>(sL + kRowBlock);                                // [kRowBlock]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = blockIdx.y;
-  int b, T, tile_tok0, slice0;
+  int b, T, tile_tok0, tile_first;
   int64_t c0;
-  if (!locate_tile(a, blockIdx.x, b, c0, T, tile_tok0, slice0)) return;
+  if (!locate_tile(a, blockIdx.x, b, c0, T, tile_tok0, tile_first)) return;
   const int64_t p0 = min(max(a.probe_off[b], (int64_t)0), a.total_probe);
   const int64_t p1 = min(max(a.probe_off[b + 1], p0), a.total_probe);
   const int rows = (int)(p1 - p0) * a.G;
+  const int n_tiles = (T + kTokPerWg - 1) / kTokPerWg;
+  const int64_t part_stride = a.total_probe * a.H;
   const int tok0 = tile_tok0 + wave * kTokPerWave;
   const bool wave_active = tok0 < T;
   const float k2 = kLog2e * 0.08838834764831845f;
@@ -336,17 +302,55 @@ __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
     const int n_pad = (n_rows + 31) & ~31;
     __syncthreads();
     stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
-    for (int r = tid; r < n_pad; r += 256) {
-      float l = INFINITY;
-      int lim = 0;
-      if (r < n_rows) {
-        const int rr = r_begin + r;
-        const int i = rr / a.G, hh = rr - i * a.G;
-        l = a.lse2[(p0 + i) * a.H + g * a.G + hh];
-        lim = LIMIT ? min(T, max(0, a.probe_limit[p0 + i])) : T;
+    // log2-sum-exp of every staged row over the request: the tiles' partials folded in tile order,
+    // kFoldBatch at a time (all loads of a thread's two rows first, then per row one maximum and one
+    // rescaled sum); every workgroup of the request computes the same values
+    {
+      static_assert(kRowBlock <= 512, "a thread folds at most two staged rows");
+      const int ra = tid, rb = tid + 256;
+      const bool has_a = ra < n_rows, has_b = rb < n_rows;
+      const float2* ppa = nullptr;
+      const float2* ppb = nullptr;
+      int lim_a = 0, lim_b = 0;
+      if (has_a) {
+        const int rr = r_begin + ra, i = rr / a.G, hh = rr - i * a.G;
+        ppa = a.part + (int64_t)tile_first * part_stride + (p0 + i) * a.H + g * a.G + hh;
+        lim_a = LIMIT ? min(T, max(0, a.probe_limit[p0 + i])) : T;
       }
-      sL[r] = l;
-      sLim[r] = lim;
+      if (has_b) {
+        const int rr = r_begin + rb, i = rr / a.G, hh = rr - i * a.G;
+        ppb = a.part + (int64_t)tile_first * part_stride + (p0 + i) * a.H + g * a.G + hh;
+        lim_b = LIMIT ? min(T, max(0, a.probe_limit[p0 + i])) : T;
+      }
+      float ma = -INFINITY, za = 0.f, mb = -INFINITY, zb = 0.f;
+      for (int t0 = 0; t0 < n_tiles; t0 += kFoldBatch) {
+        float2 pa[kFoldBatch], pb[kFoldBatch];
+        if (has_a) {
+#pragma unroll
+          for (int u = 0; u < kFoldBatch; ++u) {
+            pa[u] = (t0 + u < n_tiles) ? *ppa : make_float2(-INFINITY, 0.f);
+            ppa += part_stride;               // (stays inside the workspace: n_tiles <= the tiles allocated)
+          }
+        }
+        if (has_b) {
+#pragma unroll
+          for (int u = 0; u < kFoldBatch; ++u) {
+            pb[u] = (t0 + u < n_tiles) ? *ppb : make_float2(-INFINITY, 0.f);
+            ppb += part_stride;
+          }
+          fold_partials(pb, mb, zb);
+        }
+        if (has_a) fold_partials(pa, ma, za);
+      }
+      // rows that see nothing get +inf so that exp2(logit - lse) is 0
+      if (ra < n_pad) {
+        sL[ra] = (za > 0.f) ? ma + log2f(za) : INFINITY;
+        sLim[ra] = lim_a;
+      }
+      if (rb < n_pad) {
+        sL[rb] = (zb > 0.f) ? mb + log2f(zb) : INFINITY;
+        sLim[rb] = lim_b;
+      }
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -419,24 +423,20 @@ __global__ __launch_bounds__(256) void score_zero(float* __restrict__ score, int
 
 bool use_mfma(const qcf_layer_desc& L) { return L.dtype == QCF_DTYPE_BF16 && L.head_dim == 128; }
 
-int n_slices_upper(int32_t B, int64_t total_ctx) {
-  return (int)(((total_ctx + kTokPerWg - 1) / kTokPerWg + B) * kWavesPerWg);
-}
+int64_t n_tiles_upper(int32_t B, int64_t total_ctx) { return (total_ctx + kTokPerWg - 1) / kTokPerWg + B; }
 
-struct MfmaWs { size_t part, lse2, colsum, total; };
+struct MfmaWs { size_t part, colsum, total; };
 MfmaWs mfma_ws(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t total_ctx) {
   MfmaWs w;
   w.part = 0;
-  size_t off = align_up((size_t)n_slices_upper(B, total_ctx) * total_probe * L.n_q_heads * sizeof(float2), 256);
-  w.lse2 = off;
-  off += align_up((size_t)total_probe * L.n_q_heads * sizeof(float), 256);
+  size_t off = align_up((size_t)n_tiles_upper(B, total_ctx) * total_probe * L.n_q_heads * sizeof(float2), 256);
   w.colsum = off;
   off += align_up((size_t)L.n_kv_heads * total_ctx * sizeof(float), 256);
   w.total = off;
   return w;
 }
 
-constexpr size_t kPass1Lds = (size_t)kRowSplit1 * kQStride * 2;
+constexpr size_t kPass1Lds = (size_t)kRowSplit1 * kQStride * 2 + (size_t)kWavesPerWg * kRowSplit1 * sizeof(float2);
 constexpr size_t kPass2Lds = (size_t)kRowBlock * kQStride * 2 + (size_t)kRowBlock * 8;
 
 }  // namespace
@@ -488,11 +488,9 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
   a.total_ctx = total_ctx;
   a.B = B; a.H = H; a.Hkv = Hkv; a.G = H / Hkv;
   a.part = reinterpret_cast<float2*>(static_cast<char*>(ws) + w.part);
-  a.lse2 = reinterpret_cast<float*>(static_cast<char*>(ws) + w.lse2);
   a.colsum = reinterpret_cast<float*>(static_cast<char*>(ws) + w.colsum);
   a.score = score;
-  a.n_slices = n_slices_upper(B, total_ctx);
-  const int64_t n_tiles = (total_ctx + kTokPerWg - 1) / kTokPerWg + B;
+  const int64_t n_tiles = n_tiles_upper(B, total_ctx);
   if (n_tiles > 0x7fffffff || Hkv > 65535) return fail(QCF_ERR_UNSUPPORTED, "score: grid too large");
   const dim3 grid((unsigned)n_tiles, (unsigned)Hkv), block(256);
   const int64_t red_blocks = (total_ctx + 255) / 256;
@@ -509,8 +507,6 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
     if (probe_limit) score_pass1<true><<<grid1, block, kPass1Lds, st>>>(a);
     else score_pass1<false><<<grid1, block, kPass1Lds, st>>>(a);
     QCF_TRY_LAUNCH("score pass 1");
-    score_combine<<<dim3((unsigned)((total_probe * H + 15) / 16)), dim3(256), 0, st>>>(a);
-    QCF_TRY_LAUNCH("score combine");
     if (probe_limit) score_pass2<true><<<grid, block, kPass2Lds, st>>>(a);
     else score_pass2<false><<<grid, block, kPass2Lds, st>>>(a);
     QCF_TRY_LAUNCH("score pass 2");
