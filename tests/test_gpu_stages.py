@@ -379,3 +379,51 @@ def test_attn_row_before_context_sees_nothing():
     ro, rl = orc.recompute_attn(q, np.array([3, 12]), k, v, ctx_pos0=10)
     assert torch.count_nonzero(o[0]).item() == 0 and torch.isinf(lse[0]).all()
     assert_close(to_np(o), ro, "bf16", "o")
+
+
+def test_attn_rows_in_any_order_and_repeated():
+    # the call does not need ascending positions: shuffled rows, the same position twice
+    sh = shape_bf16()
+    rng = np.random.default_rng(47)
+    T, H, Hkv, D = 900, sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    k, v = rnd(rng, (T, Hkv, D), "bf16"), rnd(rng, (T, Hkv, D), "bf16")
+    pos = rng.permutation(T)[:130].astype(np.int32)
+    pos[7] = pos[3]
+    q = rnd(rng, (len(pos), H, D), "bf16")
+    o = torch.full((len(pos), H, D), 9.0, dtype=torch.bfloat16, device=DEV)
+    qb.qcf_recompute_attn(qb.make_desc(sh), 1, to_dev(q, torch.bfloat16), i32(pos), i64([0, len(pos)]), len(pos),
+                          to_dev(k, torch.bfloat16), to_dev(v, torch.bfloat16), i64([0, T]), T, None, o, None)
+    torch.cuda.synchronize()
+    ro, _ = orc.recompute_attn(q, pos, k, v)
+    assert_close(to_np(o), ro, "bf16", "o")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_attn_random_geometry(seed):
+    # seeded sweep over head grouping, batch, lengths, row counts and position offsets (MFMA and generic paths)
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 3, 4, 8, 16]))
+    sh = shape_bf16(H=Hkv * G, Hkv=Hkv)
+    B = int(rng.integers(1, 4))
+    T_list = [int(rng.integers(1, 1400)) for _ in range(B)]
+    N_list = [int(rng.integers(0, min(T, 160) + 1)) for T in T_list]
+    pos0 = [int(rng.integers(0, 50)) for _ in range(B)]
+    say(f"attn random: Hkv={Hkv} G={G} T={T_list} N={N_list} pos0={pos0}")
+    _attn_case(sh, T_list, N_list, seed=2000 + seed, pos0=pos0, probe_rows=int(rng.integers(0, 5)))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_score_random_geometry(seed):
+    rng = np.random.default_rng(3000 + seed)
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    sh = shape_bf16(H=Hkv * G, Hkv=Hkv)
+    B = int(rng.integers(1, 4))
+    T_list = [int(rng.integers(1, 1500)) for _ in range(B)]
+    R_list = [int(rng.integers(0, 70)) for _ in range(B)]
+    limit = None
+    if seed % 2:
+        limit = [rng.integers(0, T + 1, size=R).astype(np.int32) for T, R in zip(T_list, R_list)]
+    say(f"score random: Hkv={Hkv} G={G} T={T_list} R={R_list} limit={'yes' if limit else 'no'}")
+    _score_case(sh, T_list, R_list, seed=4000 + seed, limit=limit)
