@@ -85,6 +85,34 @@ def test_rerope_keys_only_and_empty():
     qb.qcf_rerope(desc, torch.zeros(0, dtype=torch.uint8, device=DEV), 0, 0, kf, None)   # no chunks: no-op
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_rerope_random_layout(seed):
+    # seeded sweep: chunk counts on both sides of the single-kernel limit (256 table entries), lengths from 1,
+    # gaps between chunks, arbitrary local and global start positions, both pair conventions and dtypes
+    rng = np.random.default_rng(500 + seed)
+    dtype = "bf16" if seed % 2 == 0 else "f32"
+    Hkv = int(rng.choice([1, 2, 3, 8]))
+    D = 128 if dtype == "bf16" else int(rng.choice([64, 128]))
+    sh = inputs.LayerShape(256, Hkv, Hkv, D, float(rng.choice([10000.0, 500000.0])), dtype, int(seed % 3 == 0))
+    n_chunks = int(rng.choice([1, 3, 40, 300]))
+    lens = rng.integers(1, 6 if n_chunks > 100 else 90, size=n_chunks)
+    gaps = rng.integers(0, 3, size=n_chunks) * (rng.random(n_chunks) < 0.2)
+    rows = np.cumsum(np.concatenate([[0], (lens + gaps)[:-1]])) + int(gaps[0])
+    total = int(rows[-1] + lens[-1] + 2)
+    pos0 = rng.integers(0, 60000, size=n_chunks)
+    src0 = rng.integers(0, 500, size=n_chunks)
+    say(f"rerope random: {dtype} Hkv={Hkv} D={D} chunks={n_chunks} rows={total} style={sh.rope_style}")
+    chunks = [(rnd(rng, (int(n), Hkv, D), dtype), rnd(rng, (int(n), Hkv, D), dtype)) for n in lens]
+    pre = (rnd(rng, (total, Hkv, D), dtype), rnd(rng, (total, Hkv, D), dtype))
+    kf, vf = run_rerope(sh, chunks, rows.tolist(), pos0.tolist(), total, src_pos0=src0.tolist(), prefill=pre)
+    exp_k, exp_v = pre[0].astype(np.float64).copy(), pre[1].astype(np.float64).copy()
+    for (k, v), r, p, s0 in zip(chunks, rows, pos0, src0):
+        ek, _ = orc.rerope([k], None, [int(p) - int(s0)], sh.rope_base, sh.rope_style)
+        exp_k[r:r + len(k)], exp_v[r:r + len(k)] = ek, v
+    assert_close(to_np(kf), exp_k, dtype, "k_fused")
+    assert np.array_equal(to_np(vf), exp_v)
+
+
 # ------------------------------------------------------------------ score
 
 def _score_case(sh, T_list, R_list, seed, limit=None):
@@ -427,3 +455,18 @@ def test_score_random_geometry(seed):
         limit = [rng.integers(0, T + 1, size=R).astype(np.int32) for T, R in zip(T_list, R_list)]
     say(f"score random: Hkv={Hkv} G={G} T={T_list} R={R_list} limit={'yes' if limit else 'no'}")
     _score_case(sh, T_list, R_list, seed=4000 + seed, limit=limit)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_qkv_random_geometry(seed):
+    # seeded sweep over row counts, model widths (multiples of 64 take the MFMA tilings, others the generic
+    # kernel), head counts and gather on/off
+    rng = np.random.default_rng(600 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4]))
+    d_model = int(rng.choice([64, 192, 520, 1024, 2048]))
+    sh = shape_bf16(d_model=d_model, H=Hkv * G, Hkv=Hkv, style=int(seed % 2))
+    M = int(rng.integers(1, 900))
+    x_rows = M + int(rng.integers(0, 300))
+    say(f"qkv random: d_model={d_model} H={Hkv * G}/{Hkv} M={M} x_rows={x_rows}")
+    _qkv_case(sh, M, x_rows, seed=700 + seed, gather=bool(seed % 3))
