@@ -2,10 +2,13 @@
 // selector of the paper): score[j] = mean over probe rows and heads of the softmax
 // attention the context token j receives.
 //
-// bf16 / head_dim 128 path (the dense contraction runs on MFMA):
-//   pass 1  per (256-token tile, KV head, block of 128 group rows): logits of the block's probe rows
-//           against the tile (a wave keeps 64 tokens) -> per-row (max, sum-exp) partials of the tile,
-//           in the log2 domain;
+// bf16 / head_dim 128 path (the dense contraction runs on MFMA).  A workgroup of twelve waves owns a
+// 256-token tile of one KV head: the tile's keys and the group's probe rows both arrive in LDS through
+// asynchronous loads that request every 128-byte line once (loading keys straight into registers in MFMA
+// operand layout touches 64 different lines per instruction, which is what bounded the earlier version);
+// wave (tw, rg) keeps the 64 tokens of slice tw in registers and takes every third 32-row tile of the rows.
+//   pass 1  logits of the probe rows against the tile -> per-row (max, sum-exp) of the tile, in the log2
+//           domain (the four token slices folded in LDS);
 //   pass 2  every workgroup first folds the partials of its group's rows over the request's tiles into
 //           a log2-sum-exp per row (in a fixed order, so all workgroups get the same value); logits
 //           again, p = exp2(logit - lse), summed over the rows of the group -> per-KV-head column sums;
@@ -100,13 +103,16 @@ __global__ __launch_bounds__(256) void score_colmean_generic(
 // ------------------------------------------------------------------ MFMA path (bf16, d = 128)
 
 constexpr int kTokPerWave = 64;                 // tokens a wave keeps stationary in registers
-constexpr int kWavesPerWg = 4;
-constexpr int kTokPerWg = kTokPerWave * kWavesPerWg;
+constexpr int kTokWaves = 4;                    // token slices of a workgroup
+constexpr int kRowGroups = 3;                   // waves per token slice; they share out the row tiles
+constexpr int kWavesPerWg = kTokWaves * kRowGroups;
+constexpr int kThreads = 64 * kWavesPerWg;
+constexpr int kTokPerWg = kTokPerWave * kTokWaves;
 constexpr int kRowBlock = 320;                  // probe rows (of one group) staged in LDS at a time
-constexpr int kRowSplit1 = 128;                 // pass 1 only: group rows per workgroup (grid.z); its partials are
-                                                // per row, so splitting the rows costs nothing downstream and puts
-                                                // several workgroups on a compute unit
 constexpr int kQStride = 128;                   // bf16 elements per staged row (swizzled, no padding)
+constexpr size_t kQBytes = (size_t)kRowBlock * kQStride * 2;
+constexpr size_t kKBytes = (size_t)kTokPerWg * 256;
+constexpr int kFoldBatch = 16;
 
 struct ScoreArgs {
   const bf16_t* q;            // [total_probe, H, 128]
@@ -142,21 +148,16 @@ __device__ __forceinline__ bool locate_tile(const ScoreArgs& a, int wg, int& b, 
   return false;
 }
 
-// Loads the wave's 64 key rows (tokens tok0 .. tok0+63 of KV head g) as MFMA operand
-// fragments: kf[mt][ks] holds, for lane l, token mt*32 + l%32, elements 16*ks + 8*(l/32) .. +7.
-__device__ __forceinline__ void load_k_frags(const ScoreArgs& a, int64_t c0, int T, int tok0, int g,
-                                             int lane, bf16x8 kf[2][8]) {
-#pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
-    const int tok = tok0 + mt * 32 + (lane & 31);
-    const bool ok = tok < T;
-    const bf16_t* src = a.k + ((c0 + (ok ? tok : 0)) * a.Hkv + g) * 128 + 8 * (lane >> 5);
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      u32x4 r = u32x4{0u, 0u, 0u, 0u};
-      if (ok) r = *reinterpret_cast<const u32x4*>(src + 16 * ks);
-      kf[mt][ks] = __builtin_bit_cast(bf16x8, r);
-    }
+// Stages the workgroup's 256 key rows (tokens tile_tok0 .. +255 of KV head g) into LDS with asynchronous
+// direct-to-LDS loads (a 1 KB instruction = 4 token rows, every 128-byte line requested once); same row
+// layout as the probe rows below.  Tokens past the end are clamped (masked or never written later).
+__device__ __forceinline__ void stage_k_async(const ScoreArgs& a, int64_t c0, int T, int tile_tok0, int g,
+                                              unsigned char* sK, int wave, int lane) {
+  for (int j = wave; j < kTokPerWg / 4; j += kWavesPerWg) {
+    const int r = 4 * j + (lane >> 4);
+    const int tok = min(tile_tok0 + r, T - 1);
+    const int chunk = (lane & 15) ^ (r & 15);
+    load_to_lds_addr(a.k + ((c0 + tok) * a.Hkv + g) * 128 + chunk * 8, sK + j * 1024);
   }
 }
 
@@ -176,11 +177,15 @@ __device__ __forceinline__ void stage_q_async(const ScoreArgs& a, int64_t p0, in
   }
 }
 
+// Pass 1.  A workgroup = (256-token tile, KV head); wave (tw, rg) keeps the 64 tokens of slice tw in
+// registers and takes every third 32-row tile of the staged probe rows, starting with tile rg.
 template <bool LIMIT>
-__global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  float2* sPart = reinterpret_cast<float2*>(smem + (size_t)kRowSplit1 * kQStride * 2);   // [4 waves][kRowSplit1]
+  unsigned char* sK = smem + kQBytes;
+  float2* sPart = reinterpret_cast<float2*>(smem + kQBytes + kKBytes);     // [kTokWaves][kRowBlock]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tw = wave % kTokWaves, rg = wave / kTokWaves;
   const int g = blockIdx.y;
   int b, T, tile_tok0, tile_first;
   int64_t c0;
@@ -188,79 +193,88 @@ __global__ __launch_bounds__(256) void score_pass1(ScoreArgs a) {
   const int64_t p0 = min(max(a.probe_off[b], (int64_t)0), a.total_probe);
   const int64_t p1 = min(max(a.probe_off[b + 1], p0), a.total_probe);
   const int rows = (int)(p1 - p0) * a.G;         // probe rows x heads of the group
-  const int r_begin = (int)blockIdx.z * kRowSplit1;
-  if (r_begin >= rows) return;
-  const int n_rows = min(rows - r_begin, kRowSplit1);
-  const int n_pad = (n_rows + 31) & ~31;
-  const int tok0 = tile_tok0 + wave * kTokPerWave;
+  if (rows == 0) return;
+  const int tok0 = tile_tok0 + tw * kTokPerWave;
   const bool wave_active = tok0 < T;
   const float k2 = kLog2e * 0.08838834764831845f;   // log2(e) / sqrt(128)
   // byte offset of this lane's fragment (row lane%32, chunk 2*ks + lane/32) is qb0 ^ (32 * ks)
   const int qb0 = (lane & 31) * 256 + (((lane >> 5) ^ (lane & 15)) * 16);
-
-  bf16x8 kf[2][8];
-  load_k_frags(a, c0, T, tok0, g, lane, kf);
-  stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-  for (int rt = 0; rt < n_pad; rt += 32) {
-    float mx = -INFINITY, sum = 0.f;
-    if (wave_active) {
-      floatx16 acc0 = {0}, acc1 = {0};
-      const unsigned char* qrow = smem + rt * 256;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 qf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + (qb0 ^ (32 * ks))));
-        // S^T tile: rows = tokens (A = keys), columns = probe rows (B = queries)
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf, acc1, 0, 0, 0);
-      }
-      // lane owns probe row rt + lane%32; its registers hold tokens 8*(v/4) + 4*(lane/32) + v%4
-      const int r = r_begin + rt + (lane & 31);
-      int lim = T;
-      if (LIMIT && r < rows) lim = min(T, max(0, a.probe_limit[p0 + r / a.G]));
-      float s[32];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { s[v] = acc0[v]; s[16 + v] = acc1[v]; }
-      if (LIMIT || tok0 + kTokPerWave > T) {        // wave-uniform: only ragged or limited tiles compare
-#pragma unroll
-        for (int v = 0; v < 32; ++v) {
-          const int t0 = tok0 + 32 * (v >> 4) + 8 * ((v & 15) >> 2) + 4 * (lane >> 5) + (v & 3);
-          s[v] = (t0 < lim) ? s[v] : -INFINITY;
-        }
-      }
-      mx = s[0];
-#pragma unroll
-      for (int v = 1; v < 32; ++v) mx = fmaxf(mx, s[v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * k2;          // k2 > 0: scaling commutes with the maximum
-      const float m_use = (mx == -INFINITY) ? 0.f : mx;
-#pragma unroll
-      for (int v = 0; v < 32; ++v) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], k2, -m_use));
-      sum += __shfl_xor(sum, 32, 64);
-    }
-    if (lane < 32) sPart[wave * kRowSplit1 + rt + lane] = make_float2(mx, sum);
-  }
-  __syncthreads();
-  // the four waves' 64-token partials of a row fold, in wave order, into the tile's partial
   float2* part = a.part + (int64_t)blockIdx.x * (a.total_probe * a.H);
-  for (int r = tid; r < n_rows; r += 256) {
-    float2 p[kWavesPerWg];
-    float m = -INFINITY;
+
+  stage_k_async(a, c0, T, tile_tok0, g, sK, wave, lane);
+  bf16x8 kf[2][8];
+  for (int r_begin = 0; r_begin < rows; r_begin += kRowBlock) {
+    const int n_rows = min(kRowBlock, rows - r_begin);
+    const int n_pad = (n_rows + 31) & ~31;
+    __syncthreads();                        // the previous block's rows and partials are no longer read
+    stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (r_begin == 0) {
 #pragma unroll
-    for (int w = 0; w < kWavesPerWg; ++w) { p[w] = sPart[w * kRowSplit1 + r]; m = fmaxf(m, p[w].x); }
-    float z = 0.f;
+      for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-    for (int w = 0; w < kWavesPerWg; ++w)
-      if (p[w].x > -INFINITY) z += p[w].y * exp2f(p[w].x - m);
-    const int rr = r_begin + r;
-    const int i = rr / a.G, hh = rr - i * a.G;
-    part[(p0 + i) * a.H + g * a.G + hh] = make_float2(m, z);
+        for (int ks = 0; ks < 8; ++ks)
+          kf[mt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                                                      sK + (kTokPerWave * tw + 32 * mt) * 256 + (qb0 ^ (32 * ks))));
+    }
+    for (int rt = 32 * rg; rt < n_pad; rt += 32 * kRowGroups) {
+      float mx = -INFINITY, sum = 0.f;
+      if (wave_active) {
+        floatx16 acc0 = {0}, acc1 = {0};
+        const unsigned char* qrow = smem + rt * 256;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 qf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + (qb0 ^ (32 * ks))));
+          // S^T tile: rows = tokens (A = keys), columns = probe rows (B = queries)
+          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf, acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf, acc1, 0, 0, 0);
+        }
+        // lane owns probe row rt + lane%32; its registers hold tokens 8*(v/4) + 4*(lane/32) + v%4
+        const int r = r_begin + rt + (lane & 31);
+        int lim = T;
+        if (LIMIT && r < rows) lim = min(T, max(0, a.probe_limit[p0 + r / a.G]));
+        float s[32];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { s[v] = acc0[v]; s[16 + v] = acc1[v]; }
+        if (LIMIT || tok0 + kTokPerWave > T) {        // wave-uniform: only ragged or limited tiles compare
+#pragma unroll
+          for (int v = 0; v < 32; ++v) {
+            const int t0 = tok0 + 32 * (v >> 4) + 8 * ((v & 15) >> 2) + 4 * (lane >> 5) + (v & 3);
+            s[v] = (t0 < lim) ? s[v] : -INFINITY;
+          }
+        }
+        mx = s[0];
+#pragma unroll
+        for (int v = 1; v < 32; ++v) mx = fmaxf(mx, s[v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * k2;          // k2 > 0: scaling commutes with the maximum
+        const float m_use = (mx == -INFINITY) ? 0.f : mx;
+#pragma unroll
+        for (int v = 0; v < 32; ++v) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], k2, -m_use));
+        sum += __shfl_xor(sum, 32, 64);
+      }
+      if (lane < 32) sPart[tw * kRowBlock + rt + lane] = make_float2(mx, sum);
+    }
+    __syncthreads();
+    // the four token slices' partials of a row fold, in slice order, into the tile's partial
+    for (int r = tid; r < n_rows; r += kThreads) {
+      float2 p[kTokWaves];
+      float m = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kTokWaves; ++w) { p[w] = sPart[w * kRowBlock + r]; m = fmaxf(m, p[w].x); }
+      float z = 0.f;
+#pragma unroll
+      for (int w = 0; w < kTokWaves; ++w)
+        if (p[w].x > -INFINITY) z += p[w].y * exp2f(p[w].x - m);
+      const int rr = r_begin + r;
+      const int i = rr / a.G, hh = rr - i * a.G;
+      part[(p0 + i) * a.H + g * a.G + hh] = make_float2(m, z);
+    }
   }
 }
 
 // Folds a batch of (max2, sumexp2) partials, in order, into the running pair (m, z).  A partial that saw
 // nothing is (-inf, 0) and contributes 0 * exp2(-inf) = 0.
-constexpr int kFoldBatch = 32;
 __device__ __forceinline__ void fold_partials(const float2 (&p)[kFoldBatch], float& m, float& z) {
   float mn = m;
 #pragma unroll
@@ -273,12 +287,17 @@ __device__ __forceinline__ void fold_partials(const float2 (&p)[kFoldBatch], flo
   }
 }
 
+// Pass 2, same division of work; the three row groups' column sums are added in a fixed order at the end.
 template <bool LIMIT>
-__global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  float* sL = reinterpret_cast<float*>(smem + (size_t)kRowBlock * kQStride * 2);   // [kRowBlock] lse2
-  int* sLim = reinterpret_cast<int*>(sL + kRowBlock);                                // [kRowBlock]
+  unsigned char* sK = smem + kQBytes;
+  float* sL = reinterpret_cast<float*>(smem + kQBytes + kKBytes);          // [kRowBlock] log2-sum-exp
+  int* sLim = reinterpret_cast<int*>(sL + kRowBlock);                       // [kRowBlock]
+  float* sCol = reinterpret_cast<float*>(sLim + kRowBlock);                 // [kRowGroups][kTokPerWg]
+  static_assert(kRowBlock <= kThreads, "one thread folds one staged row");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tw = wave % kTokWaves, rg = wave / kTokWaves;
   const int g = blockIdx.y;
   int b, T, tile_tok0, tile_first;
   int64_t c0;
@@ -286,76 +305,60 @@ __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
   const int64_t p0 = min(max(a.probe_off[b], (int64_t)0), a.total_probe);
   const int64_t p1 = min(max(a.probe_off[b + 1], p0), a.total_probe);
   const int rows = (int)(p1 - p0) * a.G;
+  if (rows == 0) return;                 // (the reduce kernel gives such a request zeros without reading the sums)
   const int n_tiles = (T + kTokPerWg - 1) / kTokPerWg;
   const int64_t part_stride = a.total_probe * a.H;
-  const int tok0 = tile_tok0 + wave * kTokPerWave;
+  const int tok0 = tile_tok0 + tw * kTokPerWave;
   const bool wave_active = tok0 < T;
   const float k2 = kLog2e * 0.08838834764831845f;
   const int qb0 = (lane & 31) * 256 + (((lane >> 5) ^ (lane & 15)) * 16);
 
+  stage_k_async(a, c0, T, tile_tok0, g, sK, wave, lane);
   bf16x8 kf[2][8];
-  load_k_frags(a, c0, T, tok0, g, lane, kf);
-  float col0 = 0.f, col1 = 0.f;        // column sums of tokens tok0 + lane%32 and + 32
+  float col0 = 0.f, col1 = 0.f;        // column sums of tokens tok0 + lane%32 and + 32 over this wave's row tiles
 
   for (int r_begin = 0; r_begin < rows; r_begin += kRowBlock) {
     const int n_rows = min(kRowBlock, rows - r_begin);
     const int n_pad = (n_rows + 31) & ~31;
     __syncthreads();
     stage_q_async(a, p0, g, r_begin, n_rows, n_pad, smem, wave, lane);
-    // log2-sum-exp of every staged row over the request: the tiles' partials folded in tile order,
-    // kFoldBatch at a time (all loads of a thread's two rows first, then per row one maximum and one
-    // rescaled sum); every workgroup of the request computes the same values
-    {
-      static_assert(kRowBlock <= 512, "a thread folds at most two staged rows");
-      const int ra = tid, rb = tid + 256;
-      const bool has_a = ra < n_rows, has_b = rb < n_rows;
-      const float2* ppa = nullptr;
-      const float2* ppb = nullptr;
-      int lim_a = 0, lim_b = 0;
-      if (has_a) {
-        const int rr = r_begin + ra, i = rr / a.G, hh = rr - i * a.G;
-        ppa = a.part + (int64_t)tile_first * part_stride + (p0 + i) * a.H + g * a.G + hh;
-        lim_a = LIMIT ? min(T, max(0, a.probe_limit[p0 + i])) : T;
-      }
-      if (has_b) {
-        const int rr = r_begin + rb, i = rr / a.G, hh = rr - i * a.G;
-        ppb = a.part + (int64_t)tile_first * part_stride + (p0 + i) * a.H + g * a.G + hh;
-        lim_b = LIMIT ? min(T, max(0, a.probe_limit[p0 + i])) : T;
-      }
-      float ma = -INFINITY, za = 0.f, mb = -INFINITY, zb = 0.f;
-      for (int t0 = 0; t0 < n_tiles; t0 += kFoldBatch) {
-        float2 pa[kFoldBatch], pb[kFoldBatch];
-        if (has_a) {
+    // log2-sum-exp of staged row tid over the request: the tiles' partials folded in tile order, kFoldBatch
+    // at a time (all loads first, then one maximum and one rescaled sum); every workgroup of the request
+    // computes the same values
+    if (tid < n_pad) {
+      float l = INFINITY;               // rows that do not exist or see nothing: exp2(logit - lse) = 0
+      int lim = 0;
+      if (tid < n_rows) {
+        const int rr = r_begin + tid, i = rr / a.G, hh = rr - i * a.G;
+        const float2* pp = a.part + (int64_t)tile_first * part_stride + (p0 + i) * a.H + g * a.G + hh;
+        float m = -INFINITY, z = 0.f;
+        for (int t0 = 0; t0 < n_tiles; t0 += kFoldBatch) {
+          float2 p[kFoldBatch];
 #pragma unroll
           for (int u = 0; u < kFoldBatch; ++u) {
-            pa[u] = (t0 + u < n_tiles) ? *ppa : make_float2(-INFINITY, 0.f);
-            ppa += part_stride;               // (stays inside the workspace: n_tiles <= the tiles allocated)
+            p[u] = (t0 + u < n_tiles) ? *pp : make_float2(-INFINITY, 0.f);
+            pp += part_stride;          // (stays inside the workspace: n_tiles <= the tiles allocated)
           }
+          fold_partials(p, m, z);
         }
-        if (has_b) {
-#pragma unroll
-          for (int u = 0; u < kFoldBatch; ++u) {
-            pb[u] = (t0 + u < n_tiles) ? *ppb : make_float2(-INFINITY, 0.f);
-            ppb += part_stride;
-          }
-          fold_partials(pb, mb, zb);
-        }
-        if (has_a) fold_partials(pa, ma, za);
+        if (z > 0.f) l = m + log2f(z);
+        lim = LIMIT ? min(T, max(0, a.probe_limit[p0 + i])) : T;
       }
-      // rows that see nothing get +inf so that exp2(logit - lse) is 0
-      if (ra < n_pad) {
-        sL[ra] = (za > 0.f) ? ma + log2f(za) : INFINITY;
-        sLim[ra] = lim_a;
-      }
-      if (rb < n_pad) {
-        sL[rb] = (zb > 0.f) ? mb + log2f(zb) : INFINITY;
-        sLim[rb] = lim_b;
-      }
+      sL[tid] = l;
+      sLim[tid] = lim;
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    if (r_begin == 0) {
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+          kf[mt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                                                      sK + (kTokPerWave * tw + 32 * mt) * 256 + (qb0 ^ (32 * ks))));
+    }
     if (!wave_active) continue;
-    for (int rt = 0; rt < n_pad; rt += 32) {
+    for (int rt = 32 * rg; rt < n_pad; rt += 32 * kRowGroups) {
       floatx16 acc0 = {0}, acc1 = {0};
       const unsigned char* qrow = smem + rt * 256;
 #pragma unroll
@@ -393,14 +396,19 @@ __global__ __launch_bounds__(256) void score_pass2(ScoreArgs a) {
       }
     }
   }
-  if (!wave_active) return;
   col0 += __shfl_xor(col0, 32, 64);
   col1 += __shfl_xor(col1, 32, 64);
   if (lane < 32) {
-    float* dst = a.colsum + (int64_t)g * a.total_ctx + c0;
-    const int tA = tok0 + lane;
-    if (tA < T) dst[tA] = col0;
-    if (tA + 32 < T) dst[tA + 32] = col1;
+    float* sc = sCol + rg * kTokPerWg + tw * kTokPerWave;
+    sc[lane] = col0;                      // (zero for a slice past the end of the request)
+    sc[32 + lane] = col1;
+  }
+  __syncthreads();
+  if (tid < kTokPerWg && tile_tok0 + tid < T) {
+    float sum = sCol[tid];
+#pragma unroll
+    for (int r3 = 1; r3 < kRowGroups; ++r3) sum += sCol[r3 * kTokPerWg + tid];
+    a.colsum[(int64_t)g * a.total_ctx + c0 + tile_tok0 + tid] = sum;
   }
 }
 
@@ -436,8 +444,8 @@ MfmaWs mfma_ws(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t 
   return w;
 }
 
-constexpr size_t kPass1Lds = (size_t)kRowSplit1 * kQStride * 2 + (size_t)kWavesPerWg * kRowSplit1 * sizeof(float2);
-constexpr size_t kPass2Lds = (size_t)kRowBlock * kQStride * 2 + (size_t)kRowBlock * 8;
+constexpr size_t kPass1Lds = kQBytes + kKBytes + (size_t)kTokWaves * kRowBlock * sizeof(float2);
+constexpr size_t kPass2Lds = kQBytes + kKBytes + (size_t)kRowBlock * 8 + (size_t)kRowGroups * kTokPerWg * sizeof(float);
 
 }  // namespace
 
@@ -492,7 +500,7 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
   a.score = score;
   const int64_t n_tiles = n_tiles_upper(B, total_ctx);
   if (n_tiles > 0x7fffffff || Hkv > 65535) return fail(QCF_ERR_UNSUPPORTED, "score: grid too large");
-  const dim3 grid((unsigned)n_tiles, (unsigned)Hkv), block(256);
+  const dim3 grid((unsigned)n_tiles, (unsigned)Hkv), block(kThreads);
   const int64_t red_blocks = (total_ctx + 255) / 256;
 
   static std::atomic<uint64_t> lds_ok[4];
@@ -501,11 +509,8 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
   QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&score_pass2<false>), kPass2Lds, lds_ok[2]));
   QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&score_pass2<true>), kPass2Lds, lds_ok[3]));
   if (total_probe > 0) {
-    const int64_t row_splits = (total_probe * a.G + kRowSplit1 - 1) / kRowSplit1;      // upper bound over the requests
-    if (row_splits > 65535) return fail(QCF_ERR_UNSUPPORTED, "score: too many probe rows");
-    const dim3 grid1((unsigned)n_tiles, (unsigned)Hkv, (unsigned)row_splits);
-    if (probe_limit) score_pass1<true><<<grid1, block, kPass1Lds, st>>>(a);
-    else score_pass1<false><<<grid1, block, kPass1Lds, st>>>(a);
+    if (probe_limit) score_pass1<true><<<grid, block, kPass1Lds, st>>>(a);
+    else score_pass1<false><<<grid, block, kPass1Lds, st>>>(a);
     QCF_TRY_LAUNCH("score pass 1");
     if (probe_limit) score_pass2<true><<<grid, block, kPass2Lds, st>>>(a);
     else score_pass2<false><<<grid, block, kPass2Lds, st>>>(a);
