@@ -39,7 +39,7 @@ __device__ __forceinline__ int find_request(const int64_t* __restrict__ off, int
 
 template <typename T>
 __global__ __launch_bounds__(256) void score_rows_generic(
-    const T* __restrict__ q, const int64_t* __restrict__ probe_off, int64_t total_probe,
+    const T* __restrict__ q, const int64_t* __restrict__ probe_off, int64_t /*total_probe*/,
     const T* __restrict__ k, const int64_t* __restrict__ ctx_off, int64_t total_ctx, int B,
     const int32_t* __restrict__ probe_limit, int H, int Hkv, int D, float* __restrict__ P) {
   __shared__ float sq[128];
