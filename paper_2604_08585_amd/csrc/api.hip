@@ -35,6 +35,19 @@ qcf_status allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint6
   return QCF_OK;
 }
 
+int compute_unit_count() {
+  // read once (thread-safe initialisation); the launch shapes derived from it must not change between a
+  // workspace-size query and the call that uses the workspace
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    return n;
+  }();
+  return cus;
+}
+
 static qcf_status check_desc(const qcf_layer_desc* d) {
   if (!d) return fail(QCF_ERR_INVALID_ARG, "layer descriptor is NULL");
   if (d->dtype != QCF_DTYPE_F32 && d->dtype != QCF_DTYPE_BF16)

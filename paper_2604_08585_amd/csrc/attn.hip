@@ -544,14 +544,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
 // stay whole; otherwise a segment is about the average causal work of a resident workgroup.
 struct Split { int seg_tiles, n_seg_max; };
 Split choose_split(int64_t n_blocks, int64_t total_ctx) {
-  static int slots = 0;
-  if (slots == 0) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-    slots = 2 * cus;                                  // two workgroups are resident per compute unit
-  }
+  const int slots = 2 * compute_unit_count();         // two workgroups are resident per compute unit
   const int64_t n_t = std::max<int64_t>(1, (total_ctx + kBKV - 1) / kBKV);
   const int64_t per_slot = n_blocks * ((n_t + 1) / 2) / slots;     // average causal work per resident workgroup
   // a little above that average (a multiple of 4 tiles): most resident workgroups then take one whole

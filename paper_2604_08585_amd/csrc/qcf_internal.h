@@ -29,6 +29,8 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Raises a kernel's dynamic-LDS limit, once per device and kernel (`done` is a bit mask over device ids kept by
 // the caller, one per kernel; a repeated call from another thread is harmless).
 qcf_status allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done);
+// Compute units of the device that was current at the first call (256 if none could be asked).
+int compute_unit_count();
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int elem_size(int dtype) { return dtype == QCF_DTYPE_BF16 ? 2 : 4; }
 

@@ -651,13 +651,7 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
 // the launch takes (rounds of workgroups) x (time of one workgroup); the per-k-tile and fixed costs are the
 // measured ones of the two kernels on MI355X (microseconds).
 bool prefer_256_rows(int64_t M, int n_col_tiles, int K) {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-  }
+  const int cus = compute_unit_count();
   const double k_tiles = (double)K / kBK;
   const int64_t wg256 = ((M + 255) / 256) * n_col_tiles, wg128 = ((M + 127) / 128) * n_col_tiles;
   const double t256 = (double)((wg256 + cus - 1) / cus) * (0.8 * k_tiles + 15.0);
