@@ -61,8 +61,20 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
 
   uint32_t keys[SEG > 0 ? SEG : 1];
   if (SEG > 0) {
+    // a full, 16-byte aligned segment is read as vectors (a quarter of the memory instructions)
+    if (SEG % 4 == 0 && cnt == SEG && ((reinterpret_cast<uintptr_t>(s + j0) & 15u) == 0)) {
 #pragma unroll
-    for (int i = 0; i < SEG; ++i) keys[i] = (i < cnt) ? order_key(s[j0 + i]) : 0u;
+      for (int i = 0; i < SEG / 4; ++i) {
+        const float4 v = *reinterpret_cast<const float4*>(s + j0 + 4 * i);
+        keys[4 * i + 0] = order_key(v.x);
+        keys[4 * i + 1] = order_key(v.y);
+        keys[4 * i + 2] = order_key(v.z);
+        keys[4 * i + 3] = order_key(v.w);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < SEG; ++i) keys[i] = (i < cnt) ? order_key(s[j0 + i]) : 0u;
+    }
   }
 #define QCF_KEY(i) (SEG > 0 ? keys[i] : order_key(s[j0 + (i)]))
 #define QCF_FOR_KEYS(i, ...)                                   \
