@@ -12,6 +12,9 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
+constexpr int kDigitBits = 9;                 // bits resolved per pass (measured best of 8..11 at 8192 keys)
+constexpr int kBins = 1 << kDigitBits;
+constexpr int kBinsPerLane = kBins / 64;     // the first wave scans the histogram
 
 __device__ __forceinline__ uint32_t order_key(float s) {
   uint32_t u = __float_as_uint(s);
@@ -36,7 +39,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     const float* __restrict__ score, const int64_t* __restrict__ ctx_off, int64_t total_ctx,
     const int64_t* __restrict__ sel_off, int64_t total_sel, const int32_t* __restrict__ ctx_pos0,
     int32_t* __restrict__ sel_idx, int32_t* __restrict__ sel_row, int32_t* __restrict__ sel_pos) {
-  __shared__ uint32_t merged[256];
+  __shared__ uint32_t merged[kBins];
   __shared__ uint64_t wave_tot[kWaves];
   __shared__ uint32_t red_lo[kWaves], red_hi[kWaves];
   __shared__ uint32_t s_digit, s_k;
@@ -100,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
       hi = max(hi, (uint32_t)__shfl_xor((int)hi, d, 64));
     }
     if (lane == 0) { red_lo[wave] = lo; red_hi[wave] = hi; }
-    if (tid < 256) merged[tid] = 0u;
+    for (int i = tid; i < kBins; i += kThreads) merged[i] = 0u;
     __syncthreads();
     lo = red_lo[0]; hi = red_hi[0];
 #pragma unroll
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     int bits = diff ? 32 - __clz((int)diff) : 0;     // low bits in which keys may differ
     uint32_t prefix = (bits >= 32) ? 0u : (hi >> bits);   // common high part
     while (bits > 0) {
-      const int w = min(8, bits);
+      const int w = min(kDigitBits, bits);
       const int shift = bits - w;
       const uint32_t mask = (1u << w) - 1u;
       // (merged[] was cleared before the loop and is cleared again by wave 0 after each pass)
@@ -121,10 +124,14 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
       })
       __syncthreads();
       if (wave == 0) {
-        uint32_t c[4];
+        uint32_t c[kBinsPerLane];
         uint32_t tot = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { c[q] = merged[4 * lane + q]; tot += c[q]; merged[4 * lane + q] = 0u; }
+        for (int q = 0; q < kBinsPerLane; ++q) {
+          c[q] = merged[kBinsPerLane * lane + q];
+          tot += c[q];
+          merged[kBinsPerLane * lane + q] = 0u;
+        }
         uint32_t suffix = tot;               // sum over lanes >= this one
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -133,8 +140,8 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
         }
         uint32_t above = suffix - tot;       // keys with a larger digit than this lane's bins
 #pragma unroll
-        for (int q = 3; q >= 0; --q) {
-          if (above < k && k <= above + c[q]) { s_digit = 4 * lane + q; s_k = k - above; }
+        for (int q = kBinsPerLane - 1; q >= 0; --q) {
+          if (above < k && k <= above + c[q]) { s_digit = kBinsPerLane * lane + q; s_k = k - above; }
           above += c[q];
         }
       }
