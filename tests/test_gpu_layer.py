@@ -151,6 +151,31 @@ def test_repeat_layer_is_bit_stable():
         assert torch.equal(a[key].view(torch.uint8), b[key].view(torch.uint8)), key
 
 
+def test_layer_replays_from_a_captured_graph():
+    """The six calls allocate nothing, wait for nothing and clear no memory with memset nodes, so a layer can be
+    captured once and replayed: every replay, with eager work on the same buffers in between, reproduces the
+    eager layer bit for bit."""
+    wl = inputs.make_config(2, orc.PlantOps(), scale=1 / 8)
+    L = pipeline.upload(wl, DEV)
+    ref = {k: v.clone() for k, v in pipeline.fuse_layer(L).items()}     # eager (also raises the LDS limits once)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pipeline.enqueue_layer(L)
+    n = L.total_sel
+    outs = dict(k_fused=L.k_fused[:L.total_ctx], v_fused=L.v_fused[:L.total_ctx], score=L.score[:L.total_ctx],
+                sel_idx=L.sel_idx[:n], sel_row=L.sel_row[:n], sel_pos=L.sel_pos[:n], q_sel=L.q_sel[:n],
+                k_sel=L.k_sel[:n], v_sel=L.v_sel[:n], o_sel=L.o_sel[:n], lse=L.lse[:n])
+    for rep in range(3):
+        for t in outs.values():                 # eager work between the replays: spoil every output
+            t.fill_(1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for key, t in outs.items():
+            assert torch.equal(t.view(torch.uint8), ref[key].view(torch.uint8)), f"replay {rep}: {key}"
+
+
 # ------------------------------------------------------------------ full-size configurations
 
 def test_config2_full_size_bench_configuration():
