@@ -115,11 +115,11 @@ def test_rerope_random_layout(seed):
 
 # ------------------------------------------------------------------ score
 
-def _score_case(sh, T_list, R_list, seed, limit=None):
+def _score_case(sh, T_list, R_list, seed, limit=None, q_std=1.0):
     rng = np.random.default_rng(seed)
     dt = inputs.torch_dtype(sh.dtype)
     H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
-    qs = [rnd(rng, (R, H, D), sh.dtype) for R in R_list]
+    qs = [rnd(rng, (R, H, D), sh.dtype, std=q_std) for R in R_list]
     ks = [rnd(rng, (T, Hkv, D), sh.dtype) for T in T_list]
     # make a few tokens stand out so that the softmax is far from uniform
     for q, k in zip(qs, ks):
@@ -336,7 +336,7 @@ def test_scatter(dtype):
 
 # ------------------------------------------------------------------ attn
 
-def _attn_case(sh, T_list, N_list, seed, pos0=None, probe_rows=0):
+def _attn_case(sh, T_list, N_list, seed, pos0=None, probe_rows=0, q_std=1.0):
     rng = np.random.default_rng(seed)
     dt = inputs.torch_dtype(sh.dtype)
     H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
@@ -351,7 +351,7 @@ def _attn_case(sh, T_list, N_list, seed, pos0=None, probe_rows=0):
         if probe_rows and b == 0:                  # rows after the context see every token
             pos = np.concatenate([pos, T_list[b] + p0[b] + np.arange(probe_rows)])
         poss.append(pos.astype(np.int32))
-        qs.append(rnd(rng, (len(pos), H, D), sh.dtype))
+        qs.append(rnd(rng, (len(pos), H, D), sh.dtype, std=q_std))
     n_rows = [len(p) for p in poss]
     ctx_off = np.concatenate([[0], np.cumsum(T_list)])
     sel_off = np.concatenate([[0], np.cumsum(n_rows)])
@@ -470,3 +470,19 @@ def test_qkv_random_geometry(seed):
     x_rows = M + int(rng.integers(0, 300))
     say(f"qkv random: d_model={d_model} H={Hkv * G}/{Hkv} M={M} x_rows={x_rows}")
     _qkv_case(sh, M, x_rows, seed=700 + seed, gather=bool(seed % 3))
+
+
+@pytest.mark.parametrize("q_std", [0.05, 4.0, 12.0], ids=["flat", "peaky", "one-hot"])
+def test_attn_logit_range(q_std):
+    # nearly uniform rows, and rows whose logits span hundreds of units: the running reference point of the
+    # softmax moves many times along a row (its lazy update must stay exact)
+    _attn_case(shape_bf16(), [1500], [140], seed=48, q_std=q_std)
+    _attn_case(shape_f32(), [400], [40], seed=49, q_std=q_std)
+
+
+@pytest.mark.parametrize("q_std", [0.05, 4.0], ids=["flat", "peaky"])
+def test_score_logit_range(q_std):
+    # nearly uniform softmax rows, and rows dominated by a handful of tokens (partial maxima that differ by
+    # hundreds of units between tiles)
+    _score_case(shape_bf16(H=8, Hkv=2), [1300], [21], seed=17, q_std=q_std)
+    _score_case(shape_f32(), [300], [6], seed=18, q_std=q_std)
