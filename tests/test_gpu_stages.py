@@ -486,3 +486,21 @@ def test_score_logit_range(q_std):
     # hundreds of units between tiles)
     _score_case(shape_bf16(H=8, Hkv=2), [1300], [21], seed=17, q_std=q_std)
     _score_case(shape_f32(), [300], [6], seed=18, q_std=q_std)
+
+
+def test_attn_more_row_blocks_than_the_planner_holds():
+    # 4200 row blocks (G = 16: 8 selected rows per block) exceed the split planner's table, so the launch must stay
+    # unsplit; positions repeat and are unsorted; sampled rows against the oracle
+    sh = shape_bf16(H=16, Hkv=1)
+    rng = np.random.default_rng(50)
+    T, N, H, D = 100, 4200 * 8, 16, 128
+    k, v = rnd(rng, (T, 1, D), "bf16"), rnd(rng, (T, 1, D), "bf16")
+    pos = rng.integers(0, T, size=N).astype(np.int32)
+    q = rnd(rng, (N, H, D), "bf16")
+    o = torch.full((N, H, D), 9.0, dtype=torch.bfloat16, device=DEV)
+    qb.qcf_recompute_attn(qb.make_desc(sh), 1, to_dev(q, torch.bfloat16), i32(pos), i64([0, N]), N,
+                          to_dev(k, torch.bfloat16), to_dev(v, torch.bfloat16), i64([0, T]), T, None, o, None)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, N - 1], rng.choice(N, size=300, replace=False)]))
+    ro, _ = orc.recompute_attn(q[rows], pos[rows], k, v)
+    assert_close(to_np(o[torch.from_numpy(rows).to(DEV)]), ro, "bf16", "o (sampled rows)")
