@@ -106,8 +106,11 @@ qcf_status qcf_rerope(const qcf_layer_desc* desc, const qcf_chunk* chunks_dev, i
  *            softmax_j( q_probe[i,h] . k_fused[j, h/G] / sqrt(d) ), softmax over the
  * request's own context rows.  q_probe [total_probe, H, d] holds rotated queries
  * (anchor rows and user-query rows alike).  probe_limit (NULL = none): per probe row,
- * the number of leading context rows of its request it may see.  score [total_ctx]
- * float32; each request's scores sum to 1.  Deterministic: no floating-point atomics. */
+ * the number of leading context rows of its request it may see; a row that sees nothing
+ * contributes 0 (it still counts in the mean).  score [total_ctx] float32; each request's
+ * scores sum to 1 when every probe row sees at least one token (always, without
+ * probe_limit); a request without probe rows gets zeros.  Deterministic: no
+ * floating-point atomics. */
 size_t qcf_score_workspace_bytes(const qcf_layer_desc* desc, int32_t B, int64_t total_probe,
                                  int64_t total_ctx);
 qcf_status qcf_score(const qcf_layer_desc* desc, int32_t B,
@@ -132,7 +135,8 @@ qcf_status qcf_select(int32_t B, const float* score, const int64_t* ctx_off_dev,
 
 /* ---- step 4: Q/K/V of the selected tokens (Section 3.1 Phase 4, discrete token
  * recomputation).  For m < M: y = x[row(m)] . w_qkv^T, row(m) = x_gather[m] (or m when
- * x_gather is NULL; indices outside [0, x_rows) produce zero rows), split into H query
+ * x_gather is NULL; indices outside [0, x_rows) produce zero rows; x_rows must be > 0 and,
+ * without x_gather, >= M), split into H query
  * heads, H_kv key heads, H_kv value heads; rotary embedding at pos[m] on Q and K.
  * x [x_rows, d_model]; w_qkv [(H + 2 H_kv) d, d_model]; outputs q_out [M, H, d],
  * k_out / v_out [M, H_kv, d]; any output pointer may be NULL to skip that part
@@ -155,8 +159,10 @@ qcf_status qcf_scatter(const qcf_layer_desc* desc, const void* k_new, const void
  * takes the table of discrete token indices with their absolute locations).
  * o[i,h] = sum_j softmax_j( q_sel[i,h] . k_fused[j, h/G] / sqrt(d) ) v_fused[j, h/G]
  * over the context rows j of row i's request with ctx_pos0[b] + j <= sel_pos[i]
- * (ctx_pos0_dev NULL = 0).  sel_pos must be non-decreasing inside a request (as
- * qcf_select produces).  o_out [total_sel, H, d]; lse_out (may be NULL) [total_sel, H]
+ * (ctx_pos0_dev NULL = 0).  The rows of a request may come in any order and positions may
+ * repeat; ascending order (what qcf_select produces) balances the work best, because rows
+ * are processed in blocks of consecutive rows and a block runs as far as its highest
+ * position.  o_out [total_sel, H, d]; lse_out (may be NULL) [total_sel, H]
  * float32 natural-log sum-exp of the scaled logits.  A row that sees nothing gets a zero
  * output row and lse = -inf. */
 size_t qcf_recompute_attn_workspace_bytes(const qcf_layer_desc* desc, int32_t B,

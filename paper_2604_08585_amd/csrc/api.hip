@@ -215,6 +215,8 @@ qcf_status qcf_recompute_qkv(const qcf_layer_desc* desc, const void* x, int64_t 
   if (M == 0) return QCF_OK;
   if (!x_gather_dev && x_rows < M)
     return fail(QCF_ERR_INVALID_ARG, "x has %lld rows, M = %lld", (long long)x_rows, (long long)M);
+  // (the kernels replace an index outside x by row 0 and zero the result: x needs at least that row)
+  if (x_rows == 0) return fail(QCF_ERR_INVALID_ARG, "x has no rows, M = %lld", (long long)M);
   if (!q_out && !k_out && !v_out) return QCF_OK;
   QCF_TRY(need_ptr(x, "x"));
   QCF_TRY(need_ptr(w_qkv, "w_qkv"));

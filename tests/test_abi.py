@@ -77,6 +77,9 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.qcf_recompute_qkv(C.byref(d), fake, -1, None, 4, fake, fake, fake, fake, fake, fake, 1 << 20, None) == 1
     assert lib.qcf_recompute_qkv(C.byref(d), fake, 2, None, 4, fake, fake, fake, fake, fake, fake, 1 << 20, None) == 1
     assert lib.qcf_scatter(C.byref(d), fake, fake, fake, 4, fake, None, 8, None) == 1
+    # a gather table over an empty x (an index outside x falls back to row 0, which must exist)
+    assert lib.qcf_recompute_qkv(C.byref(d), fake, 0, fake, 4, fake, fake, fake, fake, fake, fake, 1 << 20, None) == 1
+    assert b"no rows" in lib.qcf_last_error()
     # rest-of-the-layer calls: sizes must be multiples of 8, the f32 / odd-shape path needs its workspace
     assert lib.qcf_linear(C.byref(d), fake, 4, 20, fake, 64, None, fake, None, 0, None) == 1
     assert lib.qcf_linear(C.byref(d), fake, 4, 64, fake, 128, None, None, None, 0, None) == 1

@@ -11,7 +11,7 @@ import torch
 from oracle import qcf_oracle as orc
 from paper_2604_08585_amd import binding as qb
 from paper_2604_08585_amd import inputs, pipeline
-from gpu_util import DEV, SCORE_REL, assert_indices_match, i32, i64, quantizer, to_dev, to_np
+from gpu_util import DEV, SCORE_REL, assert_close, assert_indices_match, i32, i64, quantizer, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -146,9 +146,14 @@ def test_two_layer_chain_with_query_rows():
 
 
 def test_chunk_caches_streamed_from_the_host_give_the_same_layers():
-    """Layers whose chunk caches arrive over a copy stream (double-buffered) produce bit-identical results to the
-    same layers run one after the other with every copy awaited."""
-    wl = inputs.make_config(1, pipeline.HipPlantOps(DEV), scale=0.25)
+    """Layers whose chunk caches arrive over a copy stream (double-buffered): every streamed layer's patched K/V
+    and attention rows against the oracle run on that layer's host caches (rerope -> qkv -> scatter -> attn on
+    the critical layer's selection), and bit-identical to the same layers run one after the other with every
+    copy awaited."""
+    wl = inputs.make_config(1, orc.PlantOps(), scale=0.25)
+    sh, req = wl.shape, wl.requests[0]
+    H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    qz = quantizer(sh.dtype)
     L = pipeline.upload(wl, DEV)
     pipeline.enqueue_layer(L)                                   # critical layer: fixes the selection
     torch.cuda.synchronize()
@@ -159,14 +164,36 @@ def test_chunk_caches_streamed_from_the_host_give_the_same_layers():
     results = {}
     for mode in (False, True):
         outs = []
-        st.run(n_layers, after_layer=lambda i: outs.append((L.k_fused.clone(), L.o_sel.clone())), overlap=mode)
+        st.run(n_layers, after_layer=lambda i: outs.append((L.k_fused.clone(), L.v_fused.clone(), L.o_sel.clone())),
+               overlap=mode)
         torch.cuda.synchronize()
         results[mode] = outs
     for i in range(n_layers):
-        assert torch.equal(results[True][i][0], results[False][i][0]), f"fused K, layer {i}"
-        assert torch.equal(results[True][i][1], results[False][i][1]), f"O rows, layer {i}"
+        for j, what in enumerate(("fused K", "fused V", "O rows")):
+            assert torch.equal(results[True][i][j], results[False][i][j]), f"{what}, layer {i}"
+
+    # oracle on every layer's host caches, with the selection the critical layer made on the GPU
+    n = L.total_sel
+    idx = L.sel_idx[:n].cpu().numpy().astype(np.int64)
+    assert n == orc.select_count(req.T, wl.ratio) and np.all(np.diff(idx) > 0)
+    bounds = np.concatenate([[0], np.cumsum(lens)])
+    q_s, k_s, v_s = orc.recompute_qkv(req.x_ctx[idx], wl.w_qkv, idx, H, Hkv, D, sh.rope_base, sh.rope_style)
+    q_s, k_s, v_s = qz(q_s), qz(k_s), qz(v_s)
+    for i in range(n_layers):
+        hk, hv = to_np(host[i][0]), to_np(host[i][1])
+        kc = [hk[bounds[c]:bounds[c + 1]] for c in range(len(lens))]
+        vc = [hv[bounds[c]:bounds[c + 1]] for c in range(len(lens))]
+        kf, vf = orc.rerope(kc, vc, [p - c.src_pos0 for p, c in zip(req.dst_pos0, req.chunks)], sh.rope_base,
+                            sh.rope_style)
+        kp, vp = orc.scatter(qz(kf), qz(vf), k_s, v_s, idx)
+        o_ref, _ = orc.recompute_attn(q_s, idx, kp, vp)
+        gk, gv, go = (to_np(t) for t in results[True][i])
+        ek = assert_close(gk[:req.T], kp, sh.dtype, f"patched K, streamed layer {i}")
+        ev = assert_close(gv[:req.T], vp, sh.dtype, f"patched V, streamed layer {i}")
+        eo = assert_close(go[:n], qz(o_ref), sh.dtype, f"O rows, streamed layer {i}")
+        say(f"  streamed layer {i}: max abs err K {ek:.3e} V {ev:.3e} O {eo:.3e}")
     # layer 0 streams the layer's own caches: the same result as the resident path
     pipeline.enqueue_layer(L, critical=False)
     torch.cuda.synchronize()
-    assert torch.equal(results[True][0][1], L.o_sel)
-    assert not torch.equal(results[True][1][1], results[True][0][1])     # other layers really hold other caches
+    assert torch.equal(results[True][0][2], L.o_sel)
+    assert not torch.equal(results[True][1][2], results[True][0][2])     # other layers really hold other caches

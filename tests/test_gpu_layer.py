@@ -178,13 +178,25 @@ def test_layer_replays_from_a_captured_graph():
 
 # ------------------------------------------------------------------ full-size configurations
 
-def test_config2_full_size_bench_configuration():
-    """The configuration bench.py times (8192 tokens, 16 ragged chunks, ratio 0.15), whole layer,
-    every output element against the oracle."""
+@pytest.mark.parametrize("ratio", [0.05, 0.15, 0.30])
+def test_config2_full_size_bench_configuration(ratio):
+    """The configuration bench.py times (8192 tokens, 16 ragged chunks) at the three recompute ratios of the
+    sweep, whole layer, every output element against the oracle.  Each ratio takes its own launch shapes (row
+    tile of the projection, key segments of the attention)."""
     wl = inputs.make_config(2, orc.PlantOps())
     assert wl.requests[0].T == 8192 and wl.requests[0].R == 80
     inputs.assert_bf16_headroom(wl)
-    check_layer(wl, 0.15)
+    L, _, _ = check_layer(wl, ratio)
+    assert L.total_sel == {0.05: 410, 0.15: 1229, 0.30: 2458}[ratio]
+
+
+def test_config1_full_size():
+    """8B-shaped layer, 8 chunks of 512 tokens, 40 probe rows, ratio 0.15: whole layer, every element."""
+    wl = inputs.make_config(1, orc.PlantOps())
+    assert wl.requests[0].T == 4096 and wl.requests[0].R == 40
+    inputs.assert_bf16_headroom(wl)
+    L, _, _ = check_layer(wl)
+    assert L.total_sel == 615
 
 
 def test_config3_full_size_sampled_rows():
