@@ -119,6 +119,20 @@ qcf_status qcf_score(const qcf_layer_desc* desc, int32_t B,
                      const int32_t* probe_limit_dev, float* score,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): qcf_score with its scratch in a buffer built
+ * into the library (QCF_SCORE_STATIC_SCRATCH_BYTES of device memory per GPU, held until the process
+ * ends).  Same arguments, results and kernels as qcf_score, without the workspace.  It allocates and frees
+ * nothing.  A problem whose qcf_score_workspace_bytes(...) exceeds the built-in buffer returns
+ * QCF_ERR_WORKSPACE_TOO_SMALL (nothing is enqueued; qcf_last_error() gives both sizes).  All calls on one
+ * GPU share that GPU's buffer: calls that may overlap in time on one GPU (different streams, or several
+ * threads) race on it; calls ordered on one stream are safe. */
+#define QCF_SCORE_STATIC_SCRATCH_BYTES (16u << 20)
+qcf_status qcf_score_static(const qcf_layer_desc* desc, int32_t B,
+                            const void* q_probe, const int64_t* probe_off_dev, int64_t total_probe,
+                            const void* k_fused, const int64_t* ctx_off_dev, int64_t total_ctx,
+                            const int32_t* probe_limit_dev, float* score, void* stream);
+
 /* ---- step 3: Top-N selection (Section 3.1 Phase 3, "Top-N"; the recompute ratio of
  * Section 3.2).  Host helper: N = ceil(ratio * T) (guarded by 1e-9), clamped to [0, T]. */
 int64_t qcf_select_count(int64_t T, double ratio);

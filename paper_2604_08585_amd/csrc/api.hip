@@ -93,6 +93,25 @@ static qcf_status need_ws(const void* ws, size_t have, size_t need) {
 
 constexpr int64_t kMaxRows = (int64_t)1 << 30;   // indices are int32
 
+qcf_status check_score_args(const qcf_layer_desc* desc, int32_t B, const void* q_probe,
+                            const int64_t* probe_off_dev, int64_t total_probe, const void* k_fused,
+                            const int64_t* ctx_off_dev, int64_t total_ctx, const int32_t* probe_limit_dev,
+                            float* score, bool* empty) {
+  *empty = false;
+  QCF_TRY(check_desc(desc));
+  if (B < 0 || total_probe < 0 || total_ctx < 0) return fail(QCF_ERR_INVALID_ARG, "negative size");
+  if (total_ctx > kMaxRows || total_probe > kMaxRows) return fail(QCF_ERR_UNSUPPORTED, "too many rows");
+  if (B > 65535) return fail(QCF_ERR_UNSUPPORTED, "B %d > 65535", B);
+  if (B == 0 || total_ctx == 0) { *empty = true; return QCF_OK; }
+  QCF_TRY(need_ptr(score, "score"));
+  QCF_TRY(need_idx_ptr(probe_off_dev, "probe_off_dev"));
+  QCF_TRY(need_idx_ptr(ctx_off_dev, "ctx_off_dev"));
+  if (total_probe > 0) QCF_TRY(need_ptr(q_probe, "q_probe"));
+  QCF_TRY(need_ptr(k_fused, "k_fused"));
+  if (probe_limit_dev) QCF_TRY(need_idx_ptr(probe_limit_dev, "probe_limit_dev"));
+  return QCF_OK;
+}
+
 }  // namespace qcf
 
 using namespace qcf;
@@ -155,17 +174,10 @@ qcf_status qcf_score(const qcf_layer_desc* desc, int32_t B, const void* q_probe,
                      const int64_t* probe_off_dev, int64_t total_probe, const void* k_fused,
                      const int64_t* ctx_off_dev, int64_t total_ctx, const int32_t* probe_limit_dev,
                      float* score, void* workspace, size_t workspace_bytes, void* stream) {
-  QCF_TRY(check_desc(desc));
-  if (B < 0 || total_probe < 0 || total_ctx < 0) return fail(QCF_ERR_INVALID_ARG, "negative size");
-  if (total_ctx > kMaxRows || total_probe > kMaxRows) return fail(QCF_ERR_UNSUPPORTED, "too many rows");
-  if (B > 65535) return fail(QCF_ERR_UNSUPPORTED, "B %d > 65535", B);
-  if (B == 0 || total_ctx == 0) return QCF_OK;
-  QCF_TRY(need_ptr(score, "score"));
-  QCF_TRY(need_idx_ptr(probe_off_dev, "probe_off_dev"));
-  QCF_TRY(need_idx_ptr(ctx_off_dev, "ctx_off_dev"));
-  if (total_probe > 0) QCF_TRY(need_ptr(q_probe, "q_probe"));
-  QCF_TRY(need_ptr(k_fused, "k_fused"));
-  if (probe_limit_dev) QCF_TRY(need_idx_ptr(probe_limit_dev, "probe_limit_dev"));
+  bool empty = false;
+  QCF_TRY(check_score_args(desc, B, q_probe, probe_off_dev, total_probe, k_fused, ctx_off_dev, total_ctx,
+                           probe_limit_dev, score, &empty));
+  if (empty) return QCF_OK;
   QCF_TRY(need_ws(workspace, workspace_bytes, score_workspace(*desc, B, total_probe, total_ctx)));
   return launch_score(*desc, B, q_probe, probe_off_dev, total_probe, k_fused, ctx_off_dev, total_ctx,
                       probe_limit_dev, score, workspace, (hipStream_t)stream);

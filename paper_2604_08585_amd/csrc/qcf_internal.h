@@ -186,6 +186,11 @@ size_t rerope_workspace(const qcf_layer_desc& L, int32_t n_chunks, int64_t total
 qcf_status launch_rerope(const qcf_layer_desc& L, const qcf_chunk* chunks, int32_t n_chunks,
                          int64_t total_rows, void* kf, void* vf, void* ws, hipStream_t st);
 
+// host-side validation shared by the two scoring entry points; *empty = nothing to do
+qcf_status check_score_args(const qcf_layer_desc* desc, int32_t B, const void* q_probe,
+                            const int64_t* probe_off_dev, int64_t total_probe, const void* k_fused,
+                            const int64_t* ctx_off_dev, int64_t total_ctx, const int32_t* probe_limit_dev,
+                            float* score, bool* empty);
 size_t score_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t total_ctx);
 qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const int64_t* probe_off,
                         int64_t total_probe, const void* k, const int64_t* ctx_off, int64_t total_ctx,

@@ -521,3 +521,53 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
 }
 
 }  // namespace qcf
+
+// ---- scoring for callers that cannot allocate -----------------------------------------------------
+// The scratch of the kernels above (tile partials and per-head column sums, or the probability rows of
+// the generic path) lives in a device array that is part of the loaded code object: every GPU the library
+// runs on holds its own copy, at its own address, until the process ends.  In host code the array's name is
+// only a handle: the device address is asked for once per device (with that device current) and kept, and
+// that pointer is what the launchers receive.
+namespace {
+
+__device__ __align__(256) unsigned char scratch[QCF_SCORE_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+qcf_status scratch_of_current_device(void** out) {
+  int dev = 0;
+  QCF_TRY(qcf::check_hip(hipGetDevice(&dev), "hipGetDevice"));
+  if (dev < 0 || dev >= kMaxDevices) return qcf::fail(QCF_ERR_UNSUPPORTED, "device id %d >= %d", dev, kMaxDevices);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    // (two threads may both ask; they get the same address)
+    QCF_TRY(qcf::check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)"));
+    if (!p) return qcf::fail(QCF_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return QCF_OK;
+}
+
+}  // namespace
+
+extern "C" qcf_status qcf_score_static(const qcf_layer_desc* desc, int32_t B, const void* q_probe,
+                                       const int64_t* probe_off_dev, int64_t total_probe, const void* k_fused,
+                                       const int64_t* ctx_off_dev, int64_t total_ctx,
+                                       const int32_t* probe_limit_dev, float* score, void* stream) {
+  bool empty = false;
+  QCF_TRY(qcf::check_score_args(desc, B, q_probe, probe_off_dev, total_probe, k_fused, ctx_off_dev, total_ctx,
+                                probe_limit_dev, score, &empty));
+  if (empty) return QCF_OK;
+  const size_t need = qcf::score_workspace(*desc, B, total_probe, total_ctx);
+  if (need > (size_t)QCF_SCORE_STATIC_SCRATCH_BYTES)
+    return qcf::fail(QCF_ERR_WORKSPACE_TOO_SMALL,
+                     "qcf_score_static: this problem needs %zu bytes of scratch, the built-in buffer has %zu; "
+                     "use qcf_score with a caller-supplied workspace",
+                     need, (size_t)QCF_SCORE_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  QCF_TRY(scratch_of_current_device(&ws));
+  return qcf::launch_score(*desc, B, q_probe, probe_off_dev, total_probe, k_fused, ctx_off_dev, total_ctx,
+                           probe_limit_dev, score, ws, (hipStream_t)stream);
+}
