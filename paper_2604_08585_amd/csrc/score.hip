@@ -412,6 +412,304 @@ __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
   }
 }
 
+// ------------------------------------------------------------------ single-kernel path
+//
+// When the whole launch is resident at once (one workgroup per compute unit, at most as many workgroups as
+// compute units) and a KV group has at most kRowBlock probe rows, one kernel does everything.  A workgroup of
+// eight waves owns a 256-token tile of one KV head; wave w keeps tokens 32w .. 32w+31 stationary and walks all
+// row tiles.  It keeps, in registers, e = 2^(logit - m) against the maximum m of its own 32 tokens for every
+// (token, row) pair of the tile: the second exponential of a two-pass scheme becomes one multiply-add by
+// 2^(m - lse) once the row's log-sum-exp over the whole request is known.
+//
+// Two hand-offs between workgroups, both through device-scope relaxed atomics on data that is itself written
+// and read with device-scope atomic stores and loads (they bypass the non-coherent caches; a wave waits for
+// its own stores to complete before it signals, so no cache-wide release or acquire fence is needed):
+//   1. the tiles of one (request, KV head) exchange their per-row (max, sum-exp): every workgroup publishes
+//      its partials, adds one to the group's arrival counter and waits until all tiles of the request have
+//      arrived (bounded wait: all workgroups of the launch are resident, so every one of them is running);
+//   2. the KV heads of one tile exchange their column sums: the last head to arrive (found with a counter; no
+//      waiting) adds the heads in head order and writes the scores.
+// All sums run in a fixed order, so the scores are bit-stable.  The counters live in a device array that the
+// loader zero-fills; the last workgroup to finish resets the ones this launch used, so every launch starts from
+// zero without a clearing kernel.  Launches take turns over kSyncSlots sets of counters.
+
+constexpr int kFusedWaves = 8;
+constexpr int kFusedThreads = 64 * kFusedWaves;
+constexpr int kFusedRowTiles = kRowBlock / 32;
+constexpr int kSyncSlots = 8;
+constexpr int kSyncWords = 1024;           // counters per slot: [0] finished workgroups, then groups, then tiles
+constexpr uint32_t kSpinLimit = 1u << 20;  // polls (a microsecond or two each) before a workgroup gives up waiting
+
+__device__ uint32_t g_sync[kSyncSlots * kSyncWords];
+
+struct FusedArgs {
+  ScoreArgs s;
+  float2* part;        // [tile][Hkv][kRowBlock] (max2, sumexp2) of the tile, published with atomic stores
+  float* colpart;      // [tile][Hkv][kTokPerWg] column sums of one KV head
+  uint32_t* sync;      // this launch's counter slot
+  int n_wg_tiles;      // tiles the grid provides (upper bound on the tiles of all requests)
+  uint32_t spin_limit;
+};
+
+__device__ __forceinline__ void publish(float2* p, float2 v) {
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), __builtin_bit_cast(uint64_t, v), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 fetch(const float2* p) {
+  return __builtin_bit_cast(float2, __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void publish(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float fetch(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// exchange between the two 32-lane halves of a wave (one vector instruction, no LDS round trip):
+// returns the value the lane 32 away holds
+__device__ __forceinline__ float other_half(float x) {
+  typedef unsigned u2v __attribute__((ext_vector_type(2)));
+  const u2v r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  // r.x = (lower half's value in both halves), r.y = (upper half's value in both halves)
+  return (threadIdx.x & 32) ? __uint_as_float(r.x) : __uint_as_float(r.y);
+}
+// sum over the 32 lanes of each half of a wave, in a fixed order; every lane of the half gets the total
+__device__ __forceinline__ float half_wave_sum(float x) {
+  x += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x128, 0xf, 0xf, false));   // row_ror:8
+  x += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x124, 0xf, 0xf, false));   // row_ror:4
+  x += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x122, 0xf, 0xf, false));   // row_ror:2
+  x += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x121, 0xf, 0xf, false));   // row_ror:1
+  typedef unsigned u2v __attribute__((ext_vector_type(2)));
+  const u2v r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r.x) + __uint_as_float(r.y);     // rows (0, 1) and (2, 3) of 16 lanes each
+}
+
+template <bool LIMIT>
+__global__ __launch_bounds__(kFusedThreads) void score_fused(FusedArgs fa) {
+  const ScoreArgs& a = fa.s;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* sK = smem + kQBytes;
+  // (reused once the key fragments are in registers)
+  float2* sPart = reinterpret_cast<float2*>(sK);                            // [kFusedWaves][kRowBlock]
+  float* sL = reinterpret_cast<float*>(sK + kFusedWaves * kRowBlock * 8);   // [kRowBlock] log2-sum-exp
+  float* sCol = sL + kRowBlock;                                             // [kTokPerWg]
+  __shared__ int s_flag[2];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hf = lane >> 5, l32 = lane & 31;
+  const int g = (int)(blockIdx.x % a.Hkv);
+  const int wg_tile = (int)(blockIdx.x / a.Hkv);
+  const int n_wg = fa.n_wg_tiles * a.Hkv;
+
+  int b, T, tile_tok0, tile_first;
+  int64_t c0;
+  const bool have_tile = locate_tile(a, wg_tile, b, c0, T, tile_tok0, tile_first);
+  int rows = 0;
+  int64_t p0 = 0;
+  if (have_tile) {
+    p0 = min(max(a.probe_off[b], (int64_t)0), a.total_probe);
+    const int64_t p1 = min(max(a.probe_off[b + 1], p0), a.total_probe);
+    rows = min((int)(p1 - p0) * a.G, kRowBlock);       // (the launcher only takes this path when all rows fit)
+  }
+  const int n_tiles = have_tile ? (T + kTokPerWg - 1) / kTokPerWg : 0;
+  const int n_rt = (rows + 31) >> 5;
+  const float k2 = kLog2e * 0.08838834764831845f;   // log2(e) / sqrt(128)
+
+  float e[kFusedRowTiles][16];      // 2^(logit - m_w) of (token, row) pairs; row = 32 rt + l32
+
+  if (rows > 0) {
+    for (int j = wave; j < kTokPerWg / 4; j += kFusedWaves) {          // keys: 1 KB per instruction = 4 token rows
+      const int r = 4 * j + (lane >> 4);
+      const int tok = min(tile_tok0 + r, T - 1);
+      const int chunk = (lane & 15) ^ (r & 15);
+      load_to_lds_addr(a.k + ((c0 + tok) * a.Hkv + g) * 128 + chunk * 8, sK + j * 1024);
+    }
+    for (int j = wave; j < n_rt * 8; j += kFusedWaves) {               // probe rows of the group
+      const int r = 4 * j + (lane >> 4);
+      const int rr = min(r, rows - 1);
+      const int i = rr / a.G, hh = rr - i * a.G;
+      const int chunk = (lane & 15) ^ (r & 15);
+      load_to_lds_addr(a.q + ((p0 + i) * a.H + g * a.G + hh) * 128 + chunk * 8, smem + j * 1024);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    const int fb0 = l32 * 256 + ((hf ^ (lane & 15)) * 16);       // fragment ks of row l32 sits at fb0 ^ (32 ks)
+    bf16x8 kf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sK + (32 * wave) * 256 + (fb0 ^ (32 * ks))));
+    // probe-row fragments travel through a ring of four registers: fragment ks + 4 (or the next tile's
+    // fragment ks - 4) is requested right behind the MFMA that used the slot.  One address register per
+    // fragment index; the row tile is a constant offset of the read.
+    uint32_t qaddr[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qaddr[ks] = lds_offset_of(smem) + (uint32_t)(fb0 ^ (32 * ks));
+    auto qfrag = [&](int rt, int ks) {
+      return *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(qaddr[ks] + (uint32_t)(rt * 32 * 256));
+    };
+    u32x4 ring[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ring[i] = qfrag(0, i);
+    __syncthreads();                               // the key tile's LDS is reused from here on
+    const int tok0 = tile_tok0 + 32 * wave;
+#pragma unroll
+    for (int rt = 0; rt < kFusedRowTiles; ++rt) {
+      if (rt < n_rt) {
+        floatx16 acc = {0};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          // S^T tile: rows = tokens (A = keys), columns = probe rows (B = queries)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], __builtin_bit_cast(bf16x8, ring[ks & 3]), acc, 0, 0, 0);
+          if (ks < 4) ring[ks & 3] = qfrag(rt, ks + 4);
+          else if (rt + 1 < kFusedRowTiles) ring[ks & 3] = qfrag(rt + 1, ks - 4);   // (unused after the last tile)
+        }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {          // issue order: every read sits behind the MFMA that frees its slot
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (ks < 4 || rt + 1 < kFusedRowTiles) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        // lane owns probe row 32 rt + l32; register v is token tok0 + 8 (v/4) + 4 hf + v%4
+        float sv[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sv[v] = acc[v];
+        if (LIMIT || tok0 + 32 > T) {            // wave-uniform: only ragged or limited tiles compare
+          const int r = 32 * rt + l32;
+          int lim = T;
+          if (LIMIT && r < rows) lim = min(T, max(0, a.probe_limit[p0 + r / a.G]));
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int t0 = tok0 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            sv[v] = (t0 < lim) ? sv[v] : -INFINITY;
+          }
+        }
+        float mx = sv[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sv[v]);
+        mx = fmaxf(mx, other_half(mx)) * k2;          // k2 > 0: scaling commutes with the maximum
+        const float m_use = (mx == -INFINITY) ? 0.f : mx;
+        float sum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          e[rt][v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[v], k2, -m_use));
+          sum += e[rt][v];
+        }
+        sum += other_half(sum);
+        if (lane < 32) sPart[wave * kRowBlock + 32 * rt + lane] = make_float2(mx, sum);
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) e[rt][v] = 0.f;
+      }
+    }
+    __syncthreads();
+    // the eight token slices' partials of a row fold, in slice order, into the tile's partial
+    float2* part = fa.part + ((int64_t)wg_tile * a.Hkv + g) * kRowBlock;
+    for (int r = tid; r < rows; r += kFusedThreads) {
+      float2 p[kFusedWaves];
+      float m = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kFusedWaves; ++w) { p[w] = sPart[w * kRowBlock + r]; m = fmaxf(m, p[w].x); }
+      float z = 0.f;
+#pragma unroll
+      for (int w = 0; w < kFusedWaves; ++w)
+        if (p[w].x > -INFINITY) z += p[w].y * exp2f(p[w].x - m);
+      publish(part + r, make_float2(m, z));
+    }
+    __builtin_amdgcn_s_waitcnt(0);            // this thread's partials have reached memory
+    __syncthreads();
+    // hand-off 1: the tiles of (request b, KV head g)
+    if (tid == 0) {
+      uint32_t* cnt = fa.sync + 1 + b * a.Hkv + g;
+      __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t spins = 0;
+      while (__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)n_tiles &&
+             ++spins < fa.spin_limit)
+        __builtin_amdgcn_s_sleep(1);
+    }
+    __syncthreads();
+    // log2-sum-exp of row r over the request: the tiles' partials folded in tile order (up to 32 loads in
+    // flight per thread)
+    for (int r = tid; r < rows; r += kFusedThreads) {
+      const float2* pp = fa.part + ((int64_t)tile_first * a.Hkv + g) * kRowBlock + r;
+      const int64_t stride = (int64_t)a.Hkv * kRowBlock;
+      float m = -INFINITY, z = 0.f;
+      for (int t0 = 0; t0 < n_tiles; t0 += 2 * kFoldBatch) {
+        float2 pa[kFoldBatch], pb[kFoldBatch];
+#pragma unroll
+        for (int u = 0; u < kFoldBatch; ++u) {
+          pa[u] = (t0 + u < n_tiles) ? fetch(pp + u * stride) : make_float2(-INFINITY, 0.f);
+          pb[u] = (t0 + kFoldBatch + u < n_tiles) ? fetch(pp + (kFoldBatch + u) * stride) : make_float2(-INFINITY, 0.f);
+        }
+        pp += 2 * kFoldBatch * stride;
+        fold_partials(pa, m, z);
+        fold_partials(pb, m, z);
+      }
+      sL[r] = (z > 0.f) ? m + log2f(z) : INFINITY;      // a row that sees nothing: every weight is 0
+    }
+    for (int r = rows + tid; r < 32 * n_rt; r += kFusedThreads) sL[r] = INFINITY;
+    __syncthreads();
+    // column sums over this wave's rows: e * 2^(m_w - lse), row tiles in order, then over the lanes
+    float col[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) col[v] = 0.f;
+#pragma unroll
+    for (int rt = 0; rt < kFusedRowTiles; ++rt) {
+      if (rt < n_rt) {
+        const float l = sL[32 * rt + l32];
+        const float mw = sPart[wave * kRowBlock + 32 * rt + l32].x;
+        const float w = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - l);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) col[v] = __builtin_fmaf(e[rt][v], w, col[v]);
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) col[v] = half_wave_sum(col[v]);
+    if (l32 == 0) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sCol[32 * wave + 8 * (v >> 2) + 4 * hf + (v & 3)] = col[v];
+    }
+    __syncthreads();
+    float* colpart = fa.colpart + ((int64_t)wg_tile * a.Hkv + g) * kTokPerWg;
+    if (tid < kTokPerWg) publish(colpart + tid, sCol[tid]);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    // hand-off 2: the KV heads of this tile; the last one to arrive adds them up.  The count of finished
+    // workgroups is sent right behind (its operand depends on the first counter's answer, so the two
+    // additions cannot pass each other) and its answer is only looked at after the sums.
+    uint32_t fin = 0;
+    if (tid == 0) {
+      uint32_t* cnt = fa.sync + 1 + a.B * a.Hkv + wg_tile;
+      const uint32_t old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_flag[0] = (old == (uint32_t)a.Hkv - 1u) ? 1 : 0;
+      fin = __hip_atomic_fetch_add(fa.sync, 1u + (old >> 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (s_flag[0] && tid < kTokPerWg && tile_tok0 + tid < T) {
+      const float* cp = fa.colpart + (int64_t)wg_tile * a.Hkv * kTokPerWg + tid;
+      float acc = 0.f;
+      for (int gg = 0; gg < a.Hkv; ++gg) acc += fetch(cp + gg * kTokPerWg);
+      a.score[c0 + tile_tok0 + tid] = acc / (float)((rows / a.G) * a.H);
+    }
+    if (tid == 0) s_flag[1] = (fin == (uint32_t)n_wg - 1u) ? 1 : 0;
+    __syncthreads();
+  } else {
+    // a request without probe rows scores zero everywhere
+    if (have_tile && g == 0 && tid < kTokPerWg && tile_tok0 + tid < T) a.score[c0 + tile_tok0 + tid] = 0.f;
+    if (tid == 0) {
+      const uint32_t fin = __hip_atomic_fetch_add(fa.sync, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_flag[1] = (fin == (uint32_t)n_wg - 1u) ? 1 : 0;
+    }
+    __syncthreads();
+  }
+  // the last workgroup of the launch to have counted itself finished puts the launch's counters back to zero
+  // (every other workgroup has used its counters by then: a workgroup counts itself after its last use)
+  if (s_flag[1]) {
+    const int n_words = 1 + a.B * a.Hkv + fa.n_wg_tiles;
+    for (int i = tid; i < n_words; i += kFusedThreads)
+      __hip_atomic_store(fa.sync + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 __global__ __launch_bounds__(256) void score_reduce(ScoreArgs a) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (j >= a.total_ctx) return;
@@ -431,7 +729,9 @@ __global__ __launch_bounds__(256) void score_zero(float* __restrict__ score, int
 
 bool use_mfma(const qcf_layer_desc& L) { return L.dtype == QCF_DTYPE_BF16 && L.head_dim == 128; }
 
-int64_t n_tiles_upper(int32_t B, int64_t total_ctx) { return (total_ctx + kTokPerWg - 1) / kTokPerWg + B; }
+// upper bound on the 256-token tiles of all requests (tiles start at request boundaries: every request adds at
+// most one partly filled tile); exact for a single request
+int64_t n_tiles_upper(int32_t B, int64_t total_ctx) { return (total_ctx + (int64_t)B * (kTokPerWg - 1)) / kTokPerWg; }
 
 struct MfmaWs { size_t part, colsum, total; };
 MfmaWs mfma_ws(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t total_ctx) {
@@ -446,10 +746,52 @@ MfmaWs mfma_ws(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t 
 
 constexpr size_t kPass1Lds = kQBytes + kKBytes + (size_t)kTokWaves * kRowBlock * sizeof(float2);
 constexpr size_t kPass2Lds = kQBytes + kKBytes + (size_t)kRowBlock * 8 + (size_t)kRowGroups * kTokPerWg * sizeof(float);
+constexpr size_t kFusedLds = kQBytes + kKBytes;
+static_assert((size_t)kFusedWaves * kRowBlock * 8 + (size_t)kRowBlock * 4 + (size_t)kTokPerWg * 4 <= kKBytes,
+              "the single-kernel path's tables fit in the key tile's LDS");
+
+// The single-kernel path needs every workgroup of the launch resident at once (one per compute unit) and all
+// probe rows of a KV group in one staged block.  The host only knows totals, so the test is on those.
+bool use_fused(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t total_ctx) {
+  if (!use_mfma(L) || total_probe <= 0) return false;
+  const int64_t G = L.n_q_heads / L.n_kv_heads;
+  const int64_t tiles = n_tiles_upper(B, total_ctx);
+  return total_probe * G <= kRowBlock && tiles * L.n_kv_heads <= compute_unit_count() &&
+         1 + (int64_t)B * L.n_kv_heads + tiles <= kSyncWords;
+}
+struct FusedWs { size_t part, colpart, total; };
+FusedWs fused_ws(const qcf_layer_desc& L, int32_t B, int64_t total_ctx) {
+  const size_t slots = (size_t)n_tiles_upper(B, total_ctx) * L.n_kv_heads;
+  FusedWs w;
+  w.part = 0;
+  w.colpart = align_up(slots * kRowBlock * sizeof(float2), 256);
+  w.total = w.colpart + align_up(slots * kTokPerWg * sizeof(float), 256);
+  return w;
+}
+
+// Device address of the zero-initialised counter array on the current device (asked for once per device).
+qcf_status sync_counters(uint32_t** out) {
+  constexpr int kMaxDev = 64;
+  static std::atomic<uint32_t*> ptr[kMaxDev];
+  int dev = 0;
+  QCF_TRY(check_hip(hipGetDevice(&dev), "hipGetDevice"));
+  if (dev < 0 || dev >= kMaxDev) return fail(QCF_ERR_UNSUPPORTED, "device id %d >= %d", dev, kMaxDev);
+  uint32_t* p = ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* q = nullptr;
+    QCF_TRY(check_hip(hipGetSymbolAddress(&q, HIP_SYMBOL(g_sync)), "hipGetSymbolAddress(g_sync)"));
+    if (!q) return fail(QCF_ERR_HIP, "hipGetSymbolAddress(g_sync) returned a null address");
+    p = static_cast<uint32_t*>(q);
+    ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return QCF_OK;
+}
 
 }  // namespace
 
 size_t score_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t total_ctx) {
+  if (use_fused(L, B, total_probe, total_ctx)) return fused_ws(L, B, total_ctx).total;
   if (use_mfma(L)) return mfma_ws(L, B, total_probe, total_ctx).total;
   return align_up((size_t)total_probe * L.n_q_heads * total_ctx * sizeof(float), 256);
 }
@@ -485,7 +827,6 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
     return check_launch("score column mean");
   }
 
-  const MfmaWs w = mfma_ws(L, B, total_probe, total_ctx);
   ScoreArgs a;
   a.q = static_cast<const bf16_t*>(q);
   a.k = static_cast<const bf16_t*>(k);
@@ -495,6 +836,30 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
   a.total_probe = total_probe;
   a.total_ctx = total_ctx;
   a.B = B; a.H = H; a.Hkv = Hkv; a.G = H / Hkv;
+  a.part = nullptr;
+  a.colsum = nullptr;
+  a.score = score;
+  if (use_fused(L, B, total_probe, total_ctx)) {
+    const FusedWs fw = fused_ws(L, B, total_ctx);
+    FusedArgs fa;
+    fa.s = a;
+    fa.part = reinterpret_cast<float2*>(static_cast<char*>(ws) + fw.part);
+    fa.colpart = reinterpret_cast<float*>(static_cast<char*>(ws) + fw.colpart);
+    fa.n_wg_tiles = (int)n_tiles_upper(B, total_ctx);
+    fa.spin_limit = kSpinLimit;
+    uint32_t* counters = nullptr;
+    QCF_TRY(sync_counters(&counters));
+    static std::atomic<uint32_t> next_slot{0};
+    fa.sync = counters + (size_t)(next_slot.fetch_add(1, std::memory_order_relaxed) % kSyncSlots) * kSyncWords;
+    static std::atomic<uint64_t> fused_lds_ok[2];
+    QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&score_fused<false>), kFusedLds, fused_lds_ok[0]));
+    QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&score_fused<true>), kFusedLds, fused_lds_ok[1]));
+    const dim3 fgrid((unsigned)(fa.n_wg_tiles * Hkv)), fblock(kFusedThreads);
+    if (probe_limit) score_fused<true><<<fgrid, fblock, kFusedLds, st>>>(fa);
+    else score_fused<false><<<fgrid, fblock, kFusedLds, st>>>(fa);
+    return check_launch("score (single kernel)");
+  }
+  const MfmaWs w = mfma_ws(L, B, total_probe, total_ctx);
   a.part = reinterpret_cast<float2*>(static_cast<char*>(ws) + w.part);
   a.colsum = reinterpret_cast<float*>(static_cast<char*>(ws) + w.colsum);
   a.score = score;
