@@ -1,12 +1,20 @@
 // Step 4: recompute Q/K/V of the selected tokens (Section 3.1 Phase 4 of the paper):
 // [Q|K|V] = X_sel W_qkv^T, rotary embedding on Q and K at the tokens' absolute positions.
 //
-// A small table kernel writes (cos, sin)(pos_m * theta_i) from float64 angles.  The bf16 path
-// is a 32x32x16-MFMA GEMM (both operands are contiguous along the contraction dimension) with
-// LDS double buffering; an output tile is 128 columns wide, i.e. whole heads, so the rotary
-// partner of every element is inside the tile and the embedding is applied in the epilogue.
+// The bf16 path is a 32x32x16-MFMA GEMM (both operands are contiguous along the contraction
+// dimension) with a ring of LDS stages; an output tile is 128 columns wide, i.e. whole heads, so
+// the rotary partner of every element is inside the tile and the embedding is applied in the
+// epilogue, which forms the rotation itself: the angle pos * theta_i is taken in turns, with the
+// frequency split in two floats and the product's rounding error recovered by a fused
+// multiply-add (a plain float32 product would be off by 1e-3 rad at 8K positions), reduced to its
+// fraction and handed to the hardware sine and cosine (inputs in turns, errors far below a bf16
+// ulp).  Positions of 2^24 and more take the same steps in float64.
 // The generic path (f32, or shapes the MFMA tiling does not cover) writes the raw product to
-// the workspace and rotates it in a second kernel.
+// the workspace and rotates it in a second kernel with a (cos, sin) table built from float64
+// angles by a small table kernel.
+#include <type_traits>
+#include <utility>
+
 #include "qcf_internal.h"
 
 namespace qcf {
@@ -208,12 +216,14 @@ constexpr int kBK = 64;                  // contraction elements per LDS stage (
 constexpr int kBN = 128;                 // output columns per workgroup (whole heads)
 constexpr int kCStride = kBN + 8;        // floats per row of the epilogue tile (rows 4 apart: 32 banks apart)
 constexpr int kStages = 3;               // ring of LDS stages filled by asynchronous loads
+constexpr size_t kRhoBytes = 64 * sizeof(float2);   // theta_i / (2 pi) of up to 64 rotary pairs, as (high, low) floats
 
 struct QkvArgs {
   const bf16_t* x;
   const bf16_t* w;
   const int32_t* gather;
-  const float2* cs;
+  const int32_t* pos;            // [M] absolute positions (rotary embedding; unused by the plain linear map)
+  double neg2_over_d_log2base;   // theta_i = 2^(i * this)
   int64_t x_rows, M;
   int d_model, H, Hkv, D;
   int m_tiles, n_tiles;
@@ -235,7 +245,8 @@ struct Tile {
   static constexpr int STAGE = (BM + kBN) * kBK * 2;      // bytes per stage
   static constexpr size_t LDS_MAIN = (size_t)kStages * STAGE;
   static constexpr size_t LDS_EPI = (size_t)BM * kCStride * 4;
-  static constexpr size_t LDS = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+  static constexpr size_t RHO = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;      // rotary frequencies (64 doubles) sit behind both
+  static constexpr size_t LDS = RHO + kRhoBytes;
   static_assert(32 * TN * WGN == kBN, "a workgroup covers 128 output columns");
   static_assert((BM / 8) % NWAVE == 0 && (kBN / 8) % NWAVE == 0, "load split");
 };
@@ -274,43 +285,84 @@ __device__ __forceinline__ void acc_to_lds(float* sC, const floatx16 (&acc)[TM][
       }
 }
 
+// Rotary frequencies in turns per position, theta_i / (2 pi) = 2^(i * c) / (2 pi), for the d/2 pairs of a head:
+// computed in float64 and kept as two floats, high + low (written by 64 threads before the barrier that precedes
+// store_tile).
+__device__ __forceinline__ void fill_rho(const QkvArgs& a, float2* sRho, int i) {
+  if (i < a.D / 2) {
+    const double rho = exp2(a.neg2_over_d_log2base * (double)i) * 0.15915494309189535;
+    const float hi = (float)rho;
+    sRho[i] = make_float2(hi, (float)(rho - (double)hi));
+  }
+}
+// (cos, sin) of pos * theta for one pair.  The angle in turns is p * (hi + lo): the product p * hi is rounded, its
+// error is exact in an FMA, and only the fraction of the rounded part matters, so the sum below is good to about
+// 1e-7 of a turn for positions below 2^24 (exactly representable in a float).
+__device__ __forceinline__ void rotary_factor(int32_t pos, float2 rho, float& c, float& sn) {
+#pragma clang fp contract(off)          // the rounded product and its error term must stay two operations
+  float fr;
+  if (pos > -(1 << 24) && pos < (1 << 24)) {
+    const float pf = (float)pos;
+    const float t_hi = pf * rho.x;
+    const float t_lo = __builtin_fmaf(pf, rho.y, __builtin_fmaf(pf, rho.x, -t_hi));
+    fr = (t_hi - floorf(t_hi)) + t_lo;
+  } else {
+    const double turns = (double)pos * ((double)rho.x + (double)rho.y);
+    fr = (float)(turns - floor(turns));
+  }
+  c = __builtin_amdgcn_cosf(fr);
+  sn = __builtin_amdgcn_sinf(fr);
+}
+
 // Epilogue, second half (after a barrier): each thread takes the same 16 columns (8 rotary pairs) of
 // BM*8/NTHR rows.  It first requests the gather indices and rotary factors of all its rows, then rotates
 // and stores two 16-byte vectors per row.
-template <int BM, int NTHR, int STYLE>
-__device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, int64_t m0, const OutTile& ot, int tid) {
-  constexpr int NT = BM * 8 / NTHR;                    // rows per thread
-  constexpr int RSTEP = NTHR / 8;                      // row distance between a thread's tasks
-  static_assert(BM * 8 % NTHR == 0, "rows per thread");
-  const int half = a.D / 2;
-  const int tk = tid & 7, r0 = tid >> 3;
-  int e0, e1, i0;
+// Column task tk (0..7) of a 128-column tile: 16 columns = 8 rotary pairs.  e0 / e1: first column of the two
+// 8-column pieces; i0: index of the first pair inside its head.
+template <int STYLE>
+__device__ __forceinline__ void column_task(const QkvArgs& a, int tk, int& e0, int& e1, int& i0) {
   if (STYLE == 0) {
     const int per_head = a.D / 16;                     // tasks per head
     const int hd = tk / per_head;
     i0 = (tk - hd * per_head) * 8;
     e0 = hd * a.D + i0;
-    e1 = e0 + half;
+    e1 = e0 + a.D / 2;
   } else {
     e0 = tk * 16;
     e1 = e0 + 8;
     i0 = (e0 % a.D) / 2;
   }
+}
+
+template <int BM, int NTHR, int STYLE>
+__device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, const float2* sRho, int64_t m0,
+                                           const OutTile& ot, int tid) {
+  constexpr int NT = BM * 8 / NTHR;                    // rows per thread
+  constexpr int RSTEP = NTHR / 8;                      // row distance between a thread's tasks
+  static_assert(BM * 8 % NTHR == 0, "rows per thread");
+  const int tk = tid & 7, r0 = tid >> 3;
+  int e0, e1, i0;
+  column_task<STYLE>(a, tk, e0, e1, i0);
   bool zero[NT];
-  u32x4 w4[NT][4];                                     // 8 (cos, sin) pairs per row, or the row's 16 residual values
+  int32_t posv[NT];
+  u32x4 w4[NT][2];                                     // the row's 16 residual values
+  float2 rho[8];                                       // frequencies of this thread's 8 pairs, in turns per position
+  if (ot.rotate) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) rho[p] = sRho[i0 + p];
+  }
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int64_t m = m0 + r0 + t * RSTEP;
     zero[t] = false;
+    posv[t] = 0;
     if (m < a.M) {
       if (a.gather) {                                  // an index outside x produces a zero row
         const int64_t idx = a.gather[m];
         zero[t] = idx < 0 || idx >= a.x_rows;
       }
       if (ot.rotate) {
-        const u32x4* my = reinterpret_cast<const u32x4*>(a.cs + m * half + i0);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) w4[t][p] = my[p];
+        posv[t] = a.pos[m];
       } else if (a.residual) {
         const bf16_t* res = a.residual + m * ot.out_cols + ot.out_col0;
         w4[t][0] = *reinterpret_cast<const u32x4*>(res + e0);
@@ -338,8 +390,8 @@ __device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, in
     if (ot.rotate) {
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
-        const float wx = __uint_as_float(w4[t][p >> 1][(p & 1) * 2]);
-        const float wy = __uint_as_float(w4[t][p >> 1][(p & 1) * 2 + 1]);
+        float wx, wy;
+        rotary_factor(posv[t], rho[p], wx, wy);
         const int ia = (STYLE == 0) ? p : 2 * p;
         const int ib = (STYLE == 0) ? p + 8 : 2 * p + 1;
         o[ia] = f[ia] * wx - f[ib] * wy;
@@ -483,9 +535,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
 
   // epilogue: the whole BM x 128 tile goes through LDS as fp32 (it fits in the ring's space)
   float* sC = reinterpret_cast<float*>(smem);
+  float2* sRho = reinterpret_cast<float2*>(smem + C::RHO);
+  if (ot.rotate && tid < 64) fill_rho(a, sRho, tid);
   acc_to_lds<TM, TN>(sC, acc, wm * 32 * TM, wn * 32 * TN, lane);
   __syncthreads();
-  store_tile<C::BM, C::NTHR, STYLE>(a, sC, m0, ot, tid);
+  store_tile<C::BM, C::NTHR, STYLE>(a, sC, sRho, m0, ot, tid);
 }
 
 // ---- specialised variant for 256-row tiles ---------------------------------------------------------
@@ -509,7 +563,8 @@ struct WsTile {
   static constexpr int STAGE = (BM + kBN) * kBK * 2;
   static constexpr size_t LDS_MAIN = (size_t)kStages * STAGE;
   static constexpr size_t LDS_EPI = (size_t)BM * kCStride * 4;
-  static constexpr size_t LDS = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+  static constexpr size_t RHO = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+  static constexpr size_t LDS = RHO + kRhoBytes;
   static_assert(32 * TN == kBN, "a compute wave covers the 128 output columns");
 };
 
@@ -529,6 +584,7 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
   if (!ot.out) return;
   const int nk = a.d_model / kBK;
   float* sC = reinterpret_cast<float*>(smem);
+  float2* sRho = reinterpret_cast<float2*>(smem + C::RHO);
 
   if (wave >= C::NC) {
     // ---------------- load wave lw: instruction i covers tile rows 8*(lw + NL*i) .. +7
@@ -583,6 +639,7 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
       }
       __syncthreads();                                           // barrier kt + 1: tile kt + 1 has landed
     }
+    if (ot.rotate && lw == 0) fill_rho(a, sRho, lane);           // (behind the ring: no stage is touched)
     __syncthreads();                                             // the accumulators are in LDS
   } else {
     // ---------------- compute wave: rows 64*wave .. +63 of the tile, all 128 columns
@@ -644,7 +701,7 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
     acc_to_lds<TM, TN>(sC, acc, wave * 32 * TM, 0, lane);
     __syncthreads();
   }
-  store_tile<C::BM, C::NTHR, STYLE>(a, sC, m0, ot, tid);
+  store_tile<C::BM, C::NTHR, STYLE>(a, sC, sRho, m0, ot, tid);
 }
 
 // 256-row tiles (load/compute-split kernel) or 128-row tiles?  Both run one workgroup per compute unit, so
@@ -717,17 +774,13 @@ qcf_status launch_rope_table(const int32_t* pos, int64_t M, int head_dim, double
 }
 
 size_t qkv_workspace(const qcf_layer_desc& L, int64_t M) {
-  size_t bytes = cs_bytes(L, M);
-  if (!use_mfma(L))
-    bytes += align_up((size_t)M * (L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim * sizeof(float), 256);
-  return bytes;
+  if (use_mfma(L)) return 0;                       // the GEMM's epilogue forms the rotary factors itself
+  return cs_bytes(L, M) + align_up((size_t)M * (L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim * sizeof(float), 256);
 }
 
 qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, const int32_t* gather,
                       int64_t M, const void* w, const int32_t* pos, void* q, void* k, void* v, void* ws,
                       hipStream_t st) {
-  float2* cs = static_cast<float2*>(ws);
-  QCF_TRY(launch_rope_table(pos, M, L.head_dim, L.rope_base, cs, st));
   const int H = L.n_q_heads, Hkv = L.n_kv_heads, D = L.head_dim;
   const int Ntot = (H + 2 * Hkv) * D;
   if (use_mfma(L)) {
@@ -735,7 +788,8 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     a.x = static_cast<const bf16_t*>(x);
     a.w = static_cast<const bf16_t*>(w);
     a.gather = gather;
-    a.cs = cs;
+    a.pos = pos;
+    a.neg2_over_d_log2base = -2.0 / (double)D * std::log2(L.rope_base);
     a.x_rows = x_rows;
     a.M = M;
     a.d_model = L.d_model; a.H = H; a.Hkv = Hkv; a.D = D;
@@ -748,6 +802,8 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     if (big) return run_mfma<2, 4, 4, 1>(L, a, st);
     return run_mfma<2, 2, 2, 2>(L, a, st);
   }
+  float2* cs = static_cast<float2*>(ws);
+  QCF_TRY(launch_rope_table(pos, M, L.head_dim, L.rope_base, cs, st));
   float* y = reinterpret_cast<float*>(static_cast<char*>(ws) + cs_bytes(L, M));
   const int64_t mb = (M + 63) / 64;
   const int nb = (Ntot + 63) / 64;
@@ -794,7 +850,8 @@ qcf_status launch_linear(const qcf_layer_desc& L, const void* x, int64_t M, int3
     a.x = static_cast<const bf16_t*>(x);
     a.w = static_cast<const bf16_t*>(w);
     a.gather = nullptr;
-    a.cs = nullptr;
+    a.pos = nullptr;
+    a.neg2_over_d_log2base = 0.0;
     a.x_rows = M;
     a.M = M;
     a.d_model = K; a.H = N / kBN; a.Hkv = 0; a.D = kBN;

@@ -282,6 +282,27 @@ def test_qkv_large_tile_config_and_partial_outputs():
     _qkv_case(shape_bf16(), 70, 100, seed=23, outputs=(False, True, True))
 
 
+@pytest.mark.parametrize("style", [0, 1])
+def test_qkv_large_positions(style):
+    # the projection's epilogue forms the rotation itself: positions near and beyond 2^24 (where a float no
+    # longer holds the position exactly) up to the largest position the interface takes, both pair styles,
+    # small and large row tiles
+    sh = shape_bf16(d_model=256, H=32, Hkv=8, D=128, style=style)
+    for M, max_pos in ((90, 1 << 20), (90, (1 << 24) + 4096), (1100, (1 << 30) - 1)):
+        _qkv_case(sh, M, M + 10, seed=24 + M, max_pos=max_pos)
+    rng = np.random.default_rng(31)
+    pos = np.array([0, 1, (1 << 24) - 1, 1 << 24, (1 << 24) + 1, (1 << 30) - 1, 123456789, 8191], dtype=np.int32)
+    M = len(pos)
+    x = rnd(rng, (M, sh.d_model), "bf16")
+    w = rnd(rng, (sh.qkv_rows, sh.d_model), "bf16", std=1 / math.sqrt(sh.d_model))
+    q = torch.zeros((M, sh.n_q_heads, sh.head_dim), dtype=torch.bfloat16, device=DEV)
+    qb.qcf_recompute_qkv(qb.make_desc(sh), to_dev(x, torch.bfloat16), M, None, M, to_dev(w, torch.bfloat16), i32(pos),
+                         q, None, None)
+    torch.cuda.synchronize()
+    rq, _, _ = orc.recompute_qkv(x, w, pos, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_base, style)
+    assert np.all(np.abs(to_np(q) - rq) <= 2.0 ** -8 * np.abs(rq) + 2e-4)
+
+
 def test_qkv_activation_matrix_beyond_4_gib():
     # rows are gathered from both sides of the 4 GiB line of x: byte offsets no longer fit 32 bits, so the
     # launcher must take the tiling that addresses x with 64-bit pointers
