@@ -119,6 +119,20 @@ qcf_status qcf_score(const qcf_layer_desc* desc, int32_t B,
                      const int32_t* probe_limit_dev, float* score,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Scoring over several layers (Section 2 and Section 3.3 of the paper: the selectors it compares its critical-layer
+ * analysis with rank tokens by the attention of all layers, or of the last layer with probes that have not seen
+ * the context).  Same computation as qcf_score for one layer, blended into what `score` already holds:
+ *   score[j] = beta * score[j] + alpha * (this call's mean attention on token j)
+ * beta = 0 ignores (never reads) the old contents.  A sum over L layers is L calls, the first with beta = 0 and the
+ * others with beta = 1; alpha = 1 / L gives the mean (the ranking does not depend on a positive common factor).
+ * The last-layer variant is one call on the last layer's keys with probe rows projected from the bare query.
+ * Workspace as for qcf_score.  Deterministic. */
+qcf_status qcf_score_accumulate(const qcf_layer_desc* desc, int32_t B,
+                                const void* q_probe, const int64_t* probe_off_dev, int64_t total_probe,
+                                const void* k_fused, const int64_t* ctx_off_dev, int64_t total_ctx,
+                                const int32_t* probe_limit_dev, float alpha, float beta, float* score,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 /* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): qcf_score with its scratch in a buffer built
  * into the library (QCF_SCORE_STATIC_SCRATCH_BYTES of device memory per GPU, held until the process

@@ -144,6 +144,24 @@ def score(q_probe: np.ndarray, k_fused: np.ndarray,
     return out / (R * H)
 
 
+def score_layers(q_probes: Sequence[np.ndarray], k_layers: Sequence[np.ndarray],
+                 weights: Optional[Sequence[float]] = None) -> np.ndarray:
+    """Token scores from the attention of several layers: sum_l weights[l] * score(q_probes[l], k_layers[l]).
+
+    Section 2 of the paper describes selectors that rank tokens by the attention of all layers, or of the last
+    layer with probes that never saw the context (Section 3.3 compares the critical-layer analysis with both).
+    They use the same per-layer quantity as `score`; all layers = equal weights over every layer, last layer =
+    one term.  weights default to 1 / L (the mean); a common positive factor does not change the ranking.
+    """
+    L = len(k_layers)
+    assert len(q_probes) == L and L > 0
+    w = [1.0 / L] * L if weights is None else [float(x) for x in weights]
+    out = np.zeros(np.asarray(k_layers[0]).shape[0], dtype=F64)
+    for l in range(L):
+        out += w[l] * score(q_probes[l], k_layers[l])
+    return out
+
+
 # --------------------------------------------------------------------------
 # step 3: select
 # --------------------------------------------------------------------------

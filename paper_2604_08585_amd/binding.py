@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("QCF_LIB_PATH") or os.path.join(_HERE, "libqcf.so")
 EXPORTS = [
     "qcf_status_string", "qcf_last_error", "qcf_version", "qcf_select_count",
     "qcf_rerope_workspace_bytes", "qcf_rerope",
-    "qcf_score_workspace_bytes", "qcf_score", "qcf_score_static",
+    "qcf_score_workspace_bytes", "qcf_score", "qcf_score_accumulate", "qcf_score_static",
     "qcf_select_workspace_bytes", "qcf_select",
     "qcf_recompute_qkv_workspace_bytes", "qcf_recompute_qkv",
     "qcf_scatter",
@@ -73,6 +73,8 @@ def load_library() -> C.CDLL:
     lib.qcf_score_workspace_bytes.argtypes = [dp, i32, i64, i64]
     lib.qcf_score.restype = C.c_int
     lib.qcf_score.argtypes = [dp, i32, vp, vp, i64, vp, vp, i64, vp, vp, vp, sz, vp]
+    lib.qcf_score_accumulate.restype = C.c_int
+    lib.qcf_score_accumulate.argtypes = [dp, i32, vp, vp, i64, vp, vp, i64, vp, C.c_float, C.c_float, vp, vp, sz, vp]
     lib.qcf_score_static.restype = C.c_int
     lib.qcf_score_static.argtypes = [dp, i32, vp, vp, i64, vp, vp, i64, vp, vp, vp]
     lib.qcf_select_workspace_bytes.restype = sz
@@ -183,6 +185,20 @@ def qcf_score(desc: LayerDesc, B: int, q_probe: torch.Tensor, probe_off: torch.T
     wp, wn = _ws_args(workspace)
     _check(lib.qcf_score(C.byref(desc), B, _ptr(q_probe), _ptr(probe_off), total_probe, _ptr(k_fused),
                          _ptr(ctx_off), total_ctx, _ptr(probe_limit), _ptr(score), wp, wn, _stream()))
+
+
+def qcf_score_accumulate(desc: LayerDesc, B: int, q_probe: torch.Tensor, probe_off: torch.Tensor, total_probe: int,
+                         k_fused: torch.Tensor, ctx_off: torch.Tensor, total_ctx: int,
+                         probe_limit: Optional[torch.Tensor], alpha: float, beta: float, score: torch.Tensor,
+                         workspace: Optional[torch.Tensor] = None) -> None:
+    """score = beta * score + alpha * (mean attention of this layer's probe rows over its keys)."""
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(qcf_score_workspace_bytes(desc, B, total_probe, total_ctx), score.device)
+    wp, wn = _ws_args(workspace)
+    _check(lib.qcf_score_accumulate(C.byref(desc), B, _ptr(q_probe), _ptr(probe_off), total_probe, _ptr(k_fused),
+                                    _ptr(ctx_off), total_ctx, _ptr(probe_limit), float(alpha), float(beta),
+                                    _ptr(score), wp, wn, _stream()))
 
 
 def qcf_score_static(desc: LayerDesc, B: int, q_probe: torch.Tensor, probe_off: torch.Tensor, total_probe: int,

@@ -180,7 +180,22 @@ qcf_status qcf_score(const qcf_layer_desc* desc, int32_t B, const void* q_probe,
   if (empty) return QCF_OK;
   QCF_TRY(need_ws(workspace, workspace_bytes, score_workspace(*desc, B, total_probe, total_ctx)));
   return launch_score(*desc, B, q_probe, probe_off_dev, total_probe, k_fused, ctx_off_dev, total_ctx,
-                      probe_limit_dev, score, workspace, (hipStream_t)stream);
+                      probe_limit_dev, score, 1.f, 0.f, workspace, (hipStream_t)stream);
+}
+
+qcf_status qcf_score_accumulate(const qcf_layer_desc* desc, int32_t B, const void* q_probe,
+                                const int64_t* probe_off_dev, int64_t total_probe, const void* k_fused,
+                                const int64_t* ctx_off_dev, int64_t total_ctx, const int32_t* probe_limit_dev,
+                                float alpha, float beta, float* score, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  bool empty = false;
+  QCF_TRY(check_score_args(desc, B, q_probe, probe_off_dev, total_probe, k_fused, ctx_off_dev, total_ctx,
+                           probe_limit_dev, score, &empty));
+  if (!std::isfinite(alpha) || !std::isfinite(beta)) return fail(QCF_ERR_INVALID_ARG, "alpha and beta must be finite");
+  if (empty) return QCF_OK;
+  QCF_TRY(need_ws(workspace, workspace_bytes, score_workspace(*desc, B, total_probe, total_ctx)));
+  return launch_score(*desc, B, q_probe, probe_off_dev, total_probe, k_fused, ctx_off_dev, total_ctx,
+                      probe_limit_dev, score, alpha, beta, workspace, (hipStream_t)stream);
 }
 
 // ---- select ---------------------------------------------------------------------

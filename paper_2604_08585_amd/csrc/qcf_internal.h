@@ -194,7 +194,7 @@ qcf_status check_score_args(const qcf_layer_desc* desc, int32_t B, const void* q
 size_t score_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_probe, int64_t total_ctx);
 qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const int64_t* probe_off,
                         int64_t total_probe, const void* k, const int64_t* ctx_off, int64_t total_ctx,
-                        const int32_t* probe_limit, float* score, void* ws, hipStream_t st);
+                        const int32_t* probe_limit, float* score, float alpha, float beta, void* ws, hipStream_t st);
 
 size_t select_workspace(int32_t B, int64_t total_ctx);
 qcf_status launch_select(int32_t B, const float* score, const int64_t* ctx_off, int64_t total_ctx,

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void score_rows_generic(
 
 __global__ __launch_bounds__(256) void score_colmean_generic(
     const float* __restrict__ P, const int64_t* __restrict__ probe_off, int64_t total_probe,
-    const int64_t* __restrict__ ctx_off, int64_t total_ctx, int B, int H, float* __restrict__ score) {
+    const int64_t* __restrict__ ctx_off, int64_t total_ctx, int B, int H, float* score, float alpha, float beta) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (j >= total_ctx) return;
   const int b = find_request(ctx_off, B, j);
@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256) void score_colmean_generic(
   const int64_t r1 = min(max(probe_off[b + 1], r0), total_probe);
   float acc = 0.f;
   for (int64_t r = r0 * H; r < r1 * H; ++r) acc += P[r * total_ctx + j];
-  score[j] = (r1 > r0) ? acc / (float)((r1 - r0) * H) : 0.f;
+  const float sj = (r1 > r0) ? acc / (float)((r1 - r0) * H) : 0.f;
+  score[j] = (beta == 0.f) ? alpha * sj : __builtin_fmaf(beta, score[j], alpha * sj);
 }
 
 // ------------------------------------------------------------------ MFMA path (bf16, d = 128)
@@ -125,7 +126,13 @@ struct ScoreArgs {
   float2* part;               // [n_tiles][total_probe * H] (max2, sumexp2) per 256-token tile
   float* colsum;              // [Hkv][total_ctx]
   float* score;
+  float alpha, beta;          // score = beta * score + alpha * (this call's mean attention); beta == 0: plain store
 };
+
+// the one place a score is written: plain store, or blended into what is there (accumulation over layers)
+__device__ __forceinline__ void write_score(const ScoreArgs& a, int64_t j, float s) {
+  a.score[j] = (a.beta == 0.f) ? a.alpha * s : __builtin_fmaf(a.beta, a.score[j], a.alpha * s);
+}
 
 // Maps a workgroup index (= tile number over all requests) to (request, first token of its 256-token
 // tile, number of the request's first tile).  Tiles are aligned to the start of each request.  Returns
@@ -688,13 +695,13 @@ __global__ __launch_bounds__(kFusedThreads) void score_fused(FusedArgs fa) {
       const float* cp = fa.colpart + (int64_t)wg_tile * a.Hkv * kTokPerWg + tid;
       float acc = 0.f;
       for (int gg = 0; gg < a.Hkv; ++gg) acc += fetch(cp + gg * kTokPerWg);
-      a.score[c0 + tile_tok0 + tid] = acc / (float)((rows / a.G) * a.H);
+      write_score(a, c0 + tile_tok0 + tid, acc / (float)((rows / a.G) * a.H));
     }
     if (tid == 0) s_flag[1] = (fin == (uint32_t)n_wg - 1u) ? 1 : 0;
     __syncthreads();
   } else {
     // a request without probe rows scores zero everywhere
-    if (have_tile && g == 0 && tid < kTokPerWg && tile_tok0 + tid < T) a.score[c0 + tile_tok0 + tid] = 0.f;
+    if (have_tile && g == 0 && tid < kTokPerWg && tile_tok0 + tid < T) write_score(a, c0 + tile_tok0 + tid, 0.f);
     if (tid == 0) {
       const uint32_t fin = __hip_atomic_fetch_add(fa.sync, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_flag[1] = (fin == (uint32_t)n_wg - 1u) ? 1 : 0;
@@ -719,12 +726,12 @@ __global__ __launch_bounds__(256) void score_reduce(ScoreArgs a) {
   const int64_t p1 = min(max(a.probe_off[b + 1], p0), a.total_probe);
   float acc = 0.f;
   for (int g = 0; g < a.Hkv; ++g) acc += a.colsum[(int64_t)g * a.total_ctx + j];
-  a.score[j] = (p1 > p0) ? acc / (float)((p1 - p0) * a.H) : 0.f;
+  write_score(a, j, (p1 > p0) ? acc / (float)((p1 - p0) * a.H) : 0.f);
 }
 
-__global__ __launch_bounds__(256) void score_zero(float* __restrict__ score, int64_t n) {
+__global__ __launch_bounds__(256) void score_zero(float* score, int64_t n, float beta) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (j < n) score[j] = 0.f;
+  if (j < n) score[j] = (beta == 0.f) ? 0.f : beta * score[j];
 }
 
 bool use_mfma(const qcf_layer_desc& L) { return L.dtype == QCF_DTYPE_BF16 && L.head_dim == 128; }
@@ -798,11 +805,11 @@ size_t score_workspace(const qcf_layer_desc& L, int32_t B, int64_t total_probe, 
 
 qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const int64_t* probe_off,
                         int64_t total_probe, const void* k, const int64_t* ctx_off, int64_t total_ctx,
-                        const int32_t* probe_limit, float* score, void* ws, hipStream_t st) {
+                        const int32_t* probe_limit, float* score, float alpha, float beta, void* ws, hipStream_t st) {
   const int H = L.n_q_heads, Hkv = L.n_kv_heads, D = L.head_dim;
   if (total_probe == 0) {      // no probe rows at all: every score is 0 (no workspace was asked for)
     const int64_t blocks = (total_ctx + 255) / 256;
-    score_zero<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(score, total_ctx);
+    score_zero<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(score, total_ctx, beta);
     return check_launch("score zero");
   }
   if (!use_mfma(L)) {
@@ -823,7 +830,7 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
       QCF_TRY_LAUNCH("score rows");
     }
     score_colmean_generic<<<dim3((unsigned)col_blocks), dim3(256), 0, st>>>(P, probe_off, total_probe, ctx_off,
-                                                                           total_ctx, B, H, score);
+                                                                           total_ctx, B, H, score, alpha, beta);
     return check_launch("score column mean");
   }
 
@@ -839,6 +846,8 @@ qcf_status launch_score(const qcf_layer_desc& L, int32_t B, const void* q, const
   a.part = nullptr;
   a.colsum = nullptr;
   a.score = score;
+  a.alpha = alpha;
+  a.beta = beta;
   if (use_fused(L, B, total_probe, total_ctx)) {
     const FusedWs fw = fused_ws(L, B, total_ctx);
     FusedArgs fa;
@@ -934,5 +943,5 @@ extern "C" qcf_status qcf_score_static(const qcf_layer_desc* desc, int32_t B, co
   void* ws = nullptr;
   QCF_TRY(scratch_of_current_device(&ws));
   return qcf::launch_score(*desc, B, q_probe, probe_off_dev, total_probe, k_fused, ctx_off_dev, total_ctx,
-                           probe_limit_dev, score, ws, (hipStream_t)stream);
+                           probe_limit_dev, score, 1.f, 0.f, ws, (hipStream_t)stream);
 }

@@ -139,6 +139,23 @@ def step_attn(L: DeviceLayer) -> None:
                           L.ctx_off, L.total_ctx, None, L.o_sel, L.lse, L.ws_attn)
 
 
+def score_over_layers(desc, probes: List[torch.Tensor], keys: List[torch.Tensor], probe_off: torch.Tensor,
+                      ctx_off: torch.Tensor, weights: Optional[List[float]] = None) -> torch.Tensor:
+    """Token scores summed over layers (the all-layer selector; one layer with bare-query probes is the last-layer
+    selector): one qcf_score_accumulate call per layer into the same buffer.  probes[l] [total_probe, H, d] and
+    keys[l] [total_ctx, H_kv, d] belong to layer l; weights default to the mean."""
+    n = len(keys)
+    w = [1.0 / n] * n if weights is None else list(weights)
+    total_probe, total_ctx = int(probes[0].shape[0]), int(keys[0].shape[0])
+    B = int(probe_off.numel()) - 1
+    score = torch.empty(max(total_ctx, 1), dtype=torch.float32, device=keys[0].device)
+    ws = _ws(qb.qcf_score_workspace_bytes(desc, B, total_probe, total_ctx), keys[0].device)
+    for l in range(n):
+        qb.qcf_score_accumulate(desc, B, probes[l], probe_off, total_probe, keys[l], ctx_off, total_ctx, None,
+                                w[l], 0.0 if l == 0 else 1.0, score, ws)
+    return score[:total_ctx]
+
+
 STEPS = (("rerope", step_rerope), ("score", step_score), ("select", step_select),
          ("qkv", step_qkv), ("scatter", step_scatter), ("attn", step_attn))
 

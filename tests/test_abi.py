@@ -21,7 +21,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = qb.load_library()
     names = declared_symbols()
-    assert len(names) == 22 and set(names) == set(qb.EXPORTS)
+    assert len(names) == 23 and set(names) == set(qb.EXPORTS)
     for n in names:
         assert hasattr(lib, n), n
     assert lib.qcf_version() >= 100

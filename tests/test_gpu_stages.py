@@ -9,8 +9,8 @@ import torch
 
 from oracle import qcf_oracle as orc
 from paper_2604_08585_amd import binding as qb
-from paper_2604_08585_amd import inputs
-from gpu_util import (DEV, SCORE_REL, TOL, assert_close, i32, i64, max_abs, quantizer, run_rerope, to_dev,
+from paper_2604_08585_amd import inputs, pipeline
+from gpu_util import (DEV, SCORE_REL, TOL, assert_close, assert_indices_match, i32, i64, max_abs, quantizer, run_rerope, to_dev,
                             to_np)
 
 pytestmark = pytest.mark.gpu
@@ -183,6 +183,49 @@ def test_score_deterministic():
     a = _score_case(sh, [2000], [33], seed=16)
     b = _score_case(sh, [2000], [33], seed=16)
     assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("sh,T_list,R_list", [(shape_bf16(H=8, Hkv=2), [900], [24]),               # single-kernel path
+                                              (shape_bf16(H=16, Hkv=2), [1500], [81]),             # two-pass path
+                                              (shape_bf16(H=8, Hkv=2), [300, 64, 1025], [5, 0, 17]),
+                                              (shape_f32(), [260, 100], [9, 4])],
+                         ids=["bf16-fused", "bf16-two-pass", "bf16-batch", "f32"])
+def test_score_accumulated_over_layers(sh, T_list, R_list):
+    # the all-layer selector: one accumulate call per layer into one buffer, against the oracle's weighted sum;
+    # then the ranking made from it
+    rng = np.random.default_rng(90)
+    dt = inputs.torch_dtype(sh.dtype)
+    H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    n_layers, weights = 3, [0.5, 0.2, 0.3]
+    qs = [[rnd(rng, (R, H, D), sh.dtype) for R in R_list] for _ in range(n_layers)]
+    ks = [[rnd(rng, (T, Hkv, D), sh.dtype) for T in T_list] for _ in range(n_layers)]
+    ctx_off = np.concatenate([[0], np.cumsum(T_list)])
+    probe_off = np.concatenate([[0], np.cumsum(R_list)])
+    probes = [to_dev(np.concatenate(q), dt) for q in qs]
+    keys = [to_dev(np.concatenate(k), dt) for k in ks]
+    got = to_np(pipeline.score_over_layers(qb.make_desc(sh), probes, keys, i64(probe_off), i64(ctx_off), weights))
+    torch.cuda.synchronize()
+    for b in range(len(T_list)):
+        g = got[ctx_off[b]:ctx_off[b + 1]]
+        if R_list[b] == 0:
+            assert np.all(g == 0)
+            continue
+        ref = orc.score_layers([qs[l][b] for l in range(n_layers)], [ks[l][b] for l in range(n_layers)], weights)
+        assert np.all(np.abs(g - ref) <= SCORE_REL * ref + 1e-12), f"request {b}"
+        assert abs(g.sum() - sum(weights)) < 1e-4
+        n = orc.select_count(T_list[b], 0.2)
+        sel = torch.empty(n, dtype=torch.int32, device=DEV)
+        sc = torch.from_numpy(g.astype(np.float32)).to(DEV)
+        qb.qcf_select(1, sc, i64([0, T_list[b]]), T_list[b], i64([0, n]), n, None, sel, None, None)
+        assert_indices_match(sel.cpu().numpy(), ref, n, f"request {b}")
+    # beta = 0 never reads the buffer: a buffer of NaNs gives the single-layer score
+    T, R = T_list[0], R_list[0]
+    score = torch.full((int(ctx_off[-1]),), float("nan"), dtype=torch.float32, device=DEV)
+    qb.qcf_score_accumulate(qb.make_desc(sh), len(T_list), probes[0], i64(probe_off), int(probe_off[-1]), keys[0],
+                            i64(ctx_off), int(ctx_off[-1]), None, 1.0, 0.0, score)
+    ref0 = orc.score(qs[0][0], ks[0][0])
+    g0 = to_np(score)[:T]
+    assert np.all(np.abs(g0 - ref0) <= SCORE_REL * ref0 + 1e-12)
 
 
 # ------------------------------------------------------------------ select

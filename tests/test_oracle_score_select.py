@@ -148,3 +148,44 @@ def test_select_uses_values_not_magnitudes():
     # fp32 inputs, as the GPU produces them, keep their order
     s = np.array([1e-5, 3e-5, 2e-5, 0.0], dtype=np.float32)
     assert list(orc.select(s, 2)) == [1, 2]
+
+
+# ------------------------------------------------------------------ scores over several layers
+
+def _layers(seed, L=3, R=5, H=4, Hkv=2, d=8, T=23):
+    r = np.random.default_rng(seed)
+    return [r.standard_normal((R, H, d)) for _ in range(L)], [r.standard_normal((T, Hkv, d)) for _ in range(L)]
+
+
+def test_score_layers_mass_and_special_cases():
+    qs, ks = _layers(70)
+    s = orc.score_layers(qs, ks)
+    assert np.isclose(s.sum(), 1.0) and np.all(s >= 0)                    # a mean of distributions
+    w = [0.5, 2.0, 0.25]
+    assert np.isclose(orc.score_layers(qs, ks, w).sum(), sum(w))          # every layer carries unit mass
+    assert np.allclose(orc.score_layers(qs[:1], ks[:1], [1.0]), orc.score(qs[0], ks[0]))     # one layer = the score
+    assert np.allclose(orc.score_layers([qs[0]] * 4, [ks[0]] * 4), orc.score(qs[0], ks[0]))  # equal layers: the mean
+    # the last-layer selector is the single term of the last layer
+    assert np.allclose(orc.score_layers(qs, ks, [0.0, 0.0, 1.0]), orc.score(qs[2], ks[2]))
+
+
+def test_score_layers_is_linear_in_the_weights_and_ranking_ignores_scale():
+    qs, ks = _layers(71)
+    w1, w2 = np.array([0.2, 0.3, 0.5]), np.array([1.0, 0.0, 0.4])
+    assert np.allclose(orc.score_layers(qs, ks, w1 + w2), orc.score_layers(qs, ks, w1) + orc.score_layers(qs, ks, w2))
+    a, b = orc.score_layers(qs, ks, w1), orc.score_layers(qs, ks, 37.5 * w1)
+    for n in (1, 5, 11, 23):
+        assert np.array_equal(orc.select(a, n), orc.select(b, n))
+
+
+def test_score_layers_closed_form_two_layers():
+    # layer 0: all keys equal -> uniform 1/T whatever the probes; layer 1: one probe row, one head, logits known
+    T, d = 6, 4
+    k0 = np.tile(np.array([0.3, -1.0, 2.0, 0.5]), (T, 1, 1))
+    q0 = np.random.default_rng(72).standard_normal((3, 2, d))
+    q1 = np.zeros((1, 1, d)); q1[0, 0, 0] = 2.0                              # logit_j = 2 * k1[j, 0, 0] / sqrt(4) = k1[j,0,0]
+    k1 = np.zeros((T, 1, d)); k1[:, 0, 0] = np.array([0.0, 1.0, -1.0, 2.0, 0.5, -0.5])
+    e = np.exp(k1[:, 0, 0])
+    ref = 0.25 * np.full(T, 1.0 / T) + 3.0 * e / e.sum()
+    assert np.allclose(orc.score_layers([q0, q1], [k0, k1], [0.25, 3.0]), ref, atol=1e-14)
+
