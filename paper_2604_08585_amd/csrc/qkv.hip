@@ -542,8 +542,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
   store_tile<C::BM, C::NTHR, STYLE>(a, sC, sRho, m0, ot, tid);
 }
 
-// ---- specialised variant for 256-row tiles ---------------------------------------------------------
-// Four compute waves (one per SIMD, 64 x 128 outputs each) issue only fragment reads and MFMAs; four more
+// ---- specialised variant for 256-row tiles (TM = 2) and 128-row tiles (TM = 1) ----------------------
+// Four compute waves (one per SIMD, 32*TM x 128 outputs each) issue only fragment reads and MFMAs; four more
 // waves only issue the asynchronous global-to-LDS loads.  A wave that issues such a load can stall on the
 // memory pipeline's queue, and a stalled wave issues no MFMAs either: with the two roles in different
 // waves the matrix unit keeps running meanwhile.
@@ -554,9 +554,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qkv_mfma_kernel(QkvArgs a) {
 //   load wave:    after barrier kt it requests tile kt+2 into stage (kt+2)%3 == (kt-1)%3 (free: every
 //                 compute wave finished reading tile kt-1 before barrier kt), waits until its loads of
 //                 tile kt+1 have landed, barrier.
+template <int TM_>
 struct WsTile {
-  static constexpr int TM = 2, TN = 4, NC = 4, NL = 4;            // compute waves stacked along M
-  static constexpr int BM = 32 * TM * NC;                         // 256
+  static constexpr int TM = TM_, TN = 4, NC = 4, NL = 4;          // compute waves stacked along M
+  static constexpr int BM = 32 * TM * NC;                         // 256 (TM = 2) or 128 (TM = 1)
   static constexpr int NTHR = 64 * (NC + NL);
   static constexpr int A_LD = BM / 8 / NL;                        // 1 KB load instructions per load wave and stage
   static constexpr int B_LD = kBN / 8 / NL;
@@ -568,9 +569,9 @@ struct WsTile {
   static_assert(32 * TN == kBN, "a compute wave covers the 128 output columns");
 };
 
-template <int STYLE>
-__global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
-  using C = WsTile;
+template <int TM_, int STYLE>
+__global__ __launch_bounds__(WsTile<TM_>::NTHR) void qkv_ws_kernel(QkvArgs a) {
+  using C = WsTile<TM_>;
   constexpr int TM = C::TM, TN = C::TN;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -673,12 +674,14 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
     // issue order of one k-step: every fragment read sits behind an MFMA, so that the matrix unit is
     // already busy while the read is issued
     auto interleave = [&]() {
+      constexpr int kPairs = TM * TN < TM + TN ? TM * TN : TM + TN;
 #pragma unroll
-      for (int q = 0; q < TM + TN; ++q) {
+      for (int q = 0; q < kPairs; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one MFMA
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // one LDS read
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+      if (TM * TN > kPairs) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - kPairs, 0);
+      if (TM + TN > kPairs) __builtin_amdgcn_sched_group_barrier(0x100, TM + TN - kPairs, 0);
     };
     __syncthreads();                                             // barrier 0
     fetch(smem, 0, 0);
@@ -704,7 +707,7 @@ __global__ __launch_bounds__(WsTile::NTHR) void qkv_ws_kernel(QkvArgs a) {
   store_tile<C::BM, C::NTHR, STYLE>(a, sC, sRho, m0, ot, tid);
 }
 
-// 256-row tiles (load/compute-split kernel) or 128-row tiles?  Both run one workgroup per compute unit, so
+// 256-row or 128-row tiles (both load/compute-split)?  Both run one workgroup per compute unit, so
 // the launch takes (rounds of workgroups) x (time of one workgroup); the per-k-tile and fixed costs are the
 // measured ones of the two kernels on MI355X (microseconds).
 bool prefer_256_rows(int64_t M, int n_col_tiles, int K) {
@@ -712,7 +715,7 @@ bool prefer_256_rows(int64_t M, int n_col_tiles, int K) {
   const double k_tiles = (double)K / kBK;
   const int64_t wg256 = ((M + 255) / 256) * n_col_tiles, wg128 = ((M + 127) / 128) * n_col_tiles;
   const double t256 = (double)((wg256 + cus - 1) / cus) * (0.8 * k_tiles + 15.0);
-  const double t128 = (double)((wg128 + cus - 1) / cus) * (0.7 * k_tiles + 10.0);
+  const double t128 = (double)((wg128 + cus - 1) / cus) * (0.47 * k_tiles + 12.0);
   return t256 < t128;
 }
 
@@ -743,8 +746,9 @@ qcf_status run_mfma(const qcf_layer_desc& L, const QkvArgs& a_in, hipStream_t st
   return check_launch("qkv gemm");
 }
 
+template <int TM>
 qcf_status run_ws(const qcf_layer_desc& L, const QkvArgs& a_in, hipStream_t st) {
-  using C = WsTile;
+  using C = WsTile<TM>;
   const int64_t mt = (a_in.M + C::BM - 1) / C::BM;
   const int nt = (L.n_q_heads + 2 * L.n_kv_heads) * L.head_dim / kBN;
   const int64_t n_wg = mt * ((nt + 7) / 8) * 8;
@@ -754,10 +758,10 @@ qcf_status run_ws(const qcf_layer_desc& L, const QkvArgs& a_in, hipStream_t st) 
   a.m_tiles = (int)mt;
   a.n_tiles = nt;
   static std::atomic<uint64_t> lds_ok[2];
-  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&qkv_ws_kernel<0>), C::LDS, lds_ok[0]));
-  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&qkv_ws_kernel<1>), C::LDS, lds_ok[1]));
-  if (L.rope_style == 0) qkv_ws_kernel<0><<<grid, block, C::LDS, st>>>(a);
-  else qkv_ws_kernel<1><<<grid, block, C::LDS, st>>>(a);
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&qkv_ws_kernel<TM, 0>), C::LDS, lds_ok[0]));
+  QCF_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(&qkv_ws_kernel<TM, 1>), C::LDS, lds_ok[1]));
+  if (L.rope_style == 0) qkv_ws_kernel<TM, 0><<<grid, block, C::LDS, st>>>(a);
+  else qkv_ws_kernel<TM, 1><<<grid, block, C::LDS, st>>>(a);
   return check_launch("qkv gemm");
 }
 
@@ -797,9 +801,11 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     a.q = static_cast<bf16_t*>(q); a.k = static_cast<bf16_t*>(k); a.v = static_cast<bf16_t*>(v);
     a.plain = 0; a.residual = nullptr;
     const bool big = prefer_256_rows(M, Ntot / kBN, L.d_model);
-    // (the specialised kernel addresses x with 32-bit byte offsets)
-    if (big && (uint64_t)x_rows * (uint64_t)L.d_model * 2u < (1ull << 32)) return run_ws(L, a, st);
+    // (the specialised kernels address x with 32-bit byte offsets)
+    const bool ws_ok = (uint64_t)x_rows * (uint64_t)L.d_model * 2u < (1ull << 32);
+    if (big && ws_ok) return run_ws<2>(L, a, st);
     if (big) return run_mfma<2, 4, 4, 1>(L, a, st);
+    if (ws_ok) return run_ws<1>(L, a, st);
     return run_mfma<2, 2, 2, 2>(L, a, st);
   }
   float2* cs = static_cast<float2*>(ws);
@@ -860,8 +866,10 @@ qcf_status launch_linear(const qcf_layer_desc& L, const void* x, int64_t M, int3
     a.plain = 1;
     a.residual = static_cast<const bf16_t*>(residual);
     const bool big = prefer_256_rows(M, N / kBN, K);
-    if (big && (uint64_t)M * (uint64_t)K * 2u < (1ull << 32)) return run_ws(LL, a, st);
+    const bool ws_ok = (uint64_t)M * (uint64_t)K * 2u < (1ull << 32);
+    if (big && ws_ok) return run_ws<2>(LL, a, st);
     if (big) return run_mfma<2, 4, 4, 1>(LL, a, st);
+    if (ws_ok) return run_ws<1>(LL, a, st);
     return run_mfma<2, 2, 2, 2>(LL, a, st);
   }
   float* y = static_cast<float*>(ws);
