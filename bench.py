@@ -34,6 +34,9 @@ def parse_args():
     p.add_argument("--copies", type=int, default=6, help="independent buffer sets cycled through")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="skip the captured-graph replay leg")
+    p.add_argument("--no-separate-calls", action="store_true",
+                   help="skip the pass that times qcf_recompute_qkv and qcf_scatter as two calls (profiler runs: "
+                        "keeps the kernel statistics to the timed five-call path)")
     p.add_argument("--cpu-sample-rows", type=int, default=512,
                    help="selected rows per request the oracle times at configurations 3-4 (0-2 run in full)")
     p.add_argument("--no-tail", action="store_true",
@@ -60,6 +63,9 @@ def algorithmic_work(L, sel_pos_host, shape, requests):
         "qkv": {"bytes": (N * dm + (H + 2 * Hkv) * D * dm + N * (H + 2 * Hkv) * D) * s,
                 "flops": 2 * N * dm * (H + 2 * Hkv) * D},
         "scatter": {"bytes": 4 * N * kv_row, "flops": 0},
+        # projection and write-back in one call: the K/V rows go out twice (k_out / v_out and the cache rows)
+        "qkv_scatter": {"bytes": (N * dm + (H + 2 * Hkv) * D * dm + N * (H + 2 * Hkv) * D) * s + 2 * N * kv_row,
+                        "flops": 2 * N * dm * (H + 2 * Hkv) * D},
         "attn": {"bytes": 2 * N * H * D * s + 2 * T * kv_row, "flops": 4 * H * D * vis},
     }
 
@@ -286,11 +292,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    names = [n for n, _ in pipeline.STEPS]
-
-    def run_with_events(n_steps, first, only=None):
+    # The timed step runs the path as five calls (projection and write-back in one); the per-call table also
+    # carries the two of them as separate calls (qcf_recompute_qkv, qcf_scatter), from a pass of the six-call path.
+    def run_with_events(n_steps, first, only=None, steps=pipeline.FUSED_STEPS):
         """n_steps layers back to back; events on the launch stream (torch's current stream) bracket every
         call, or only call `only`.  Returns (wall seconds, mean ms per bracketed call)."""
+        names = [n for n, _ in steps]
         which = range(len(names)) if only is None else [names.index(only)]
         ev = [{j: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for j in which}
               for _ in range(n_steps)]
@@ -298,7 +305,7 @@ def main():
         t0 = time.perf_counter()
         for i in range(n_steps):
             L = layers[(first + i) % len(layers)]
-            for j, (_, fn) in enumerate(pipeline.STEPS):
+            for j, (_, fn) in enumerate(steps):
                 if j in ev[i]:
                     ev[i][j][0].record()
                 fn(L)
@@ -315,8 +322,14 @@ def main():
         pipeline.enqueue_layer(layers[i % len(layers)])
     torch.cuda.synchronize()
     sel_pos_host = layers[0].sel_pos[:layers[0].total_sel].cpu().numpy()
-    _, per_call = run_with_events(max(10, min(50, args.steps)), args.warmup)
-    dominant = max(names, key=lambda n: per_call[n])
+    n_inst = max(10, min(50, args.steps))
+    _, per_call = run_with_events(n_inst, args.warmup)
+    names = [n for n, _ in pipeline.FUSED_STEPS]
+    if not args.no_separate_calls:
+        _, six = run_with_events(n_inst, args.warmup, steps=pipeline.STEPS)
+        per_call["qkv"], per_call["scatter"] = six["qkv"], six["scatter"]
+        names = ["rerope", "score", "select", "qkv", "scatter", "qkv_scatter", "attn"]
+    dominant = max([n for n, _ in pipeline.FUSED_STEPS], key=lambda n: per_call[n])
 
     # timed region: exactly `steps` layers back to back, events around the dominant call only (an event
     # pair around each of the six calls costs several microseconds per layer at this scale)
@@ -341,7 +354,7 @@ def main():
             tf = work[n]["flops"] / (ms * 1e-3) / 1e12
             ent["TFLOP/s"] = round(tf, 2)
             f_mfma = tf / MFMA_BF16_PEAK_TFLOPS
-        if n in ("qkv", "attn"):
+        if n in ("qkv", "qkv_scatter", "attn"):
             ent["bound"], ent["frac"] = "mfma", round(f_mfma, 4)
         elif n == "score":
             floor_hbm = work[n]["bytes"] / (HBM_PEAK_GBS * 1e9)
@@ -354,7 +367,7 @@ def main():
         else:
             ent["bound"], ent["frac"] = "hbm", round(f_hbm, 4)
         kernels[n] = ent
-    if dominant in ("qkv", "attn", "score"):
+    if dominant in ("qkv_scatter", "attn", "score"):
         achieved = work[dominant]["flops"] / (per_call[dominant] * 1e-3) / 1e12
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(achieved, 2),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -410,12 +423,12 @@ def main():
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": shape.dtype, "data": "synthetic",
-        "config": {"workload": workload, "buffer_copies": len(layers)},
+        "config": {"workload": workload, "buffer_copies": len(layers), "calls_per_step": len(pipeline.FUSED_STEPS)},
         "roofline": roofline,
         "kernels": kernels,
         # token analysis runs once per request (critical layer only), reconstruction at every layer
         "analysis_ms": round(per_call["score"] + per_call["select"], 5),
-        "reconstruction_ms": round(per_call["rerope"] + per_call["qkv"] + per_call["scatter"] + per_call["attn"], 5),
+        "reconstruction_ms": round(per_call["rerope"] + per_call["qkv_scatter"] + per_call["attn"], 5),
         "warm_single_buffer": {"ms_per_step": round(warm_ms, 5), "value": round(total_T / (warm_ms * 1e-3), 1),
                                "steps": warm_steps, "note": "one buffer set reused every step (cache-resident); "
                                                             "not the reported value"},

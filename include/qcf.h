@@ -10,6 +10,7 @@
  *   call order for one layer:
  *     qcf_rerope -> [critical layer only: qcf_score -> qcf_select] ->
  *     qcf_recompute_qkv -> qcf_scatter -> qcf_recompute_attn
+ *   (qcf_recompute_qkv_scatter does the fourth and the fifth in one call)
  *   (attention runs after the scatter: a recomputed row must see the recomputed K/V
  *   of the other selected rows, otherwise recomputing every token would not reproduce
  *   full causal prefill - the paper's "Full Computation" end point.)
@@ -174,6 +175,18 @@ qcf_status qcf_recompute_qkv(const qcf_layer_desc* desc, const void* x, int64_t 
                              const int32_t* x_gather_dev, int64_t M, const void* w_qkv,
                              const int32_t* pos_dev, void* q_out, void* k_out, void* v_out,
                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- steps 4 and 5 in one call (Section 3.1 Phase 4: the recomputed K/V replace the stale rows of the
+ * fused cache).  Same results as qcf_recompute_qkv followed by qcf_scatter(k_out, v_out, dst_rows_dev, M,
+ * k_fused, v_fused, total_rows): q_out / k_out / v_out as above (k_out and v_out are required here), and row
+ * dst_rows[m] of k_fused / v_fused <- row m of k_out / v_out (rows outside [0, total_rows) are skipped;
+ * dst_rows must not repeat).  On the bf16 MFMA path the cache rows are written from the projection's epilogue,
+ * without a second pass over them.  Workspace: qcf_recompute_qkv_workspace_bytes. */
+qcf_status qcf_recompute_qkv_scatter(const qcf_layer_desc* desc, const void* x, int64_t x_rows,
+                                     const int32_t* x_gather_dev, int64_t M, const void* w_qkv,
+                                     const int32_t* pos_dev, void* q_out, void* k_out, void* v_out,
+                                     const int32_t* dst_rows_dev, void* k_fused, void* v_fused,
+                                     int64_t total_rows, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- step 5: write the recomputed K/V rows into the fused cache (Section 3.1 Phase 4,
  * "updated" KV).  Row dst_rows[m] of k_fused / v_fused <- row m of k_new / v_new; rows

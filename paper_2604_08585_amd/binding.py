@@ -20,7 +20,7 @@ EXPORTS = [
     "qcf_rerope_workspace_bytes", "qcf_rerope",
     "qcf_score_workspace_bytes", "qcf_score", "qcf_score_accumulate", "qcf_score_static",
     "qcf_select_workspace_bytes", "qcf_select",
-    "qcf_recompute_qkv_workspace_bytes", "qcf_recompute_qkv",
+    "qcf_recompute_qkv_workspace_bytes", "qcf_recompute_qkv", "qcf_recompute_qkv_scatter",
     "qcf_scatter",
     "qcf_recompute_attn_workspace_bytes", "qcf_recompute_attn",
     "qcf_linear_workspace_bytes", "qcf_linear", "qcf_rmsnorm", "qcf_swiglu",
@@ -85,6 +85,8 @@ def load_library() -> C.CDLL:
     lib.qcf_recompute_qkv_workspace_bytes.argtypes = [dp, i64]
     lib.qcf_recompute_qkv.restype = C.c_int
     lib.qcf_recompute_qkv.argtypes = [dp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.qcf_recompute_qkv_scatter.restype = C.c_int
+    lib.qcf_recompute_qkv_scatter.argtypes = [dp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     lib.qcf_scatter.restype = C.c_int
     lib.qcf_scatter.argtypes = [dp, vp, vp, vp, i64, vp, vp, i64, vp]
     lib.qcf_recompute_attn_workspace_bytes.restype = sz
@@ -240,6 +242,20 @@ def qcf_recompute_qkv(desc: LayerDesc, x: torch.Tensor, x_rows: int, x_gather: O
     wp, wn = _ws_args(workspace)
     _check(lib.qcf_recompute_qkv(C.byref(desc), _ptr(x), x_rows, _ptr(x_gather), M, _ptr(w_qkv), _ptr(pos),
                                  _ptr(q_out), _ptr(k_out), _ptr(v_out), wp, wn, _stream()))
+
+
+def qcf_recompute_qkv_scatter(desc: LayerDesc, x: torch.Tensor, x_rows: int, x_gather: Optional[torch.Tensor],
+                              M: int, w_qkv: torch.Tensor, pos: torch.Tensor, q_out: Optional[torch.Tensor],
+                              k_out: torch.Tensor, v_out: torch.Tensor, dst_rows: torch.Tensor,
+                              k_fused: torch.Tensor, v_fused: torch.Tensor, total_rows: int,
+                              workspace: Optional[torch.Tensor] = None) -> None:
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(qcf_recompute_qkv_workspace_bytes(desc, M), x.device)
+    wp, wn = _ws_args(workspace)
+    _check(lib.qcf_recompute_qkv_scatter(C.byref(desc), _ptr(x), x_rows, _ptr(x_gather), M, _ptr(w_qkv), _ptr(pos),
+                                         _ptr(q_out), _ptr(k_out), _ptr(v_out), _ptr(dst_rows), _ptr(k_fused),
+                                         _ptr(v_fused), total_rows, wp, wn, _stream()))
 
 
 def qcf_scatter(desc: LayerDesc, k_new: torch.Tensor, v_new: Optional[torch.Tensor], dst_rows: torch.Tensor,

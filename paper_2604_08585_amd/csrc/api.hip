@@ -253,8 +253,35 @@ qcf_status qcf_recompute_qkv(const qcf_layer_desc* desc, const void* x, int64_t 
   QCF_TRY(opt_ptr(k_out, "k_out"));
   QCF_TRY(opt_ptr(v_out, "v_out"));
   QCF_TRY(need_ws(workspace, workspace_bytes, qkv_workspace(*desc, M)));
-  return launch_qkv(*desc, x, x_rows, x_gather_dev, M, w_qkv, pos_dev, q_out, k_out, v_out, workspace,
-                    (hipStream_t)stream);
+  return launch_qkv(*desc, x, x_rows, x_gather_dev, M, w_qkv, pos_dev, q_out, k_out, v_out, nullptr, nullptr,
+                    nullptr, 0, workspace, (hipStream_t)stream);
+}
+
+qcf_status qcf_recompute_qkv_scatter(const qcf_layer_desc* desc, const void* x, int64_t x_rows,
+                                     const int32_t* x_gather_dev, int64_t M, const void* w_qkv,
+                                     const int32_t* pos_dev, void* q_out, void* k_out, void* v_out,
+                                     const int32_t* dst_rows_dev, void* k_fused, void* v_fused,
+                                     int64_t total_rows, void* workspace, size_t workspace_bytes, void* stream) {
+  QCF_TRY(check_desc(desc));
+  if (M < 0 || x_rows < 0 || total_rows < 0) return fail(QCF_ERR_INVALID_ARG, "negative size");
+  if (M > kMaxRows || x_rows > kMaxRows || total_rows > kMaxRows) return fail(QCF_ERR_UNSUPPORTED, "too many rows");
+  if (M == 0) return QCF_OK;
+  if (!x_gather_dev && x_rows < M)
+    return fail(QCF_ERR_INVALID_ARG, "x has %lld rows, M = %lld", (long long)x_rows, (long long)M);
+  if (x_rows == 0) return fail(QCF_ERR_INVALID_ARG, "x has no rows, M = %lld", (long long)M);
+  QCF_TRY(need_ptr(x, "x"));
+  QCF_TRY(need_ptr(w_qkv, "w_qkv"));
+  QCF_TRY(need_idx_ptr(pos_dev, "pos_dev"));
+  if (x_gather_dev) QCF_TRY(need_idx_ptr(x_gather_dev, "x_gather_dev"));
+  QCF_TRY(opt_ptr(q_out, "q_out"));
+  QCF_TRY(need_ptr(k_out, "k_out"));
+  QCF_TRY(need_ptr(v_out, "v_out"));
+  QCF_TRY(need_idx_ptr(dst_rows_dev, "dst_rows_dev"));
+  QCF_TRY(need_ptr(k_fused, "k_fused"));
+  QCF_TRY(need_ptr(v_fused, "v_fused"));
+  QCF_TRY(need_ws(workspace, workspace_bytes, qkv_workspace(*desc, M)));
+  return launch_qkv(*desc, x, x_rows, x_gather_dev, M, w_qkv, pos_dev, q_out, k_out, v_out, dst_rows_dev, k_fused,
+                    v_fused, total_rows, workspace, (hipStream_t)stream);
 }
 
 // ---- scatter --------------------------------------------------------------------

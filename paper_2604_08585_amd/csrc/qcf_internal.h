@@ -203,8 +203,10 @@ qcf_status launch_select(int32_t B, const float* score, const int64_t* ctx_off, 
                          hipStream_t st);
 
 size_t qkv_workspace(const qcf_layer_desc& L, int64_t M);
+// dst_rows / k_fused / v_fused (all or none): the K/V rows are also written to rows dst_rows[m] of the fused cache
 qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, const int32_t* gather,
                       int64_t M, const void* w, const int32_t* pos, void* q, void* k, void* v,
+                      const int32_t* dst_rows, void* k_fused, void* v_fused, int64_t fused_rows,
                       void* ws, hipStream_t st);
 
 qcf_status launch_scatter(const qcf_layer_desc& L, const void* k_new, const void* v_new,

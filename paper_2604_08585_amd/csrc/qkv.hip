@@ -233,6 +233,12 @@ struct QkvArgs {
   // plain linear map (qcf_linear): all H*D columns go to q without rotation; residual (may be NULL) is added
   int plain;
   const bf16_t* residual;
+  // projection fused with the write-back: row m of the K and V tiles also goes to row dst_rows[m] of the fused
+  // cache (rows outside [0, fused_rows) are skipped); all null / 0 otherwise
+  const int32_t* dst_rows;
+  bf16_t* k_fused;
+  bf16_t* v_fused;
+  int64_t fused_rows;
 };
 
 template <int TM, int TN, int WGM, int WGN>
@@ -254,6 +260,7 @@ struct Tile {
 // Where a 128-column tile of the fused projection goes.
 struct OutTile {
   bf16_t* out;
+  bf16_t* fused;          // second destination, addressed through dst_rows (K and V tiles of the fused call)
   int out_cols, out_col0;
   bool rotate;
 };
@@ -261,9 +268,10 @@ __device__ __forceinline__ OutTile out_tile_of(const QkvArgs& a, int col0) {
   const int q_cols = a.H * a.D, kv_cols = a.Hkv * a.D;
   OutTile o;
   o.rotate = !a.plain;
+  o.fused = nullptr;
   if (col0 < q_cols) { o.out = a.q; o.out_cols = q_cols; o.out_col0 = col0; }
-  else if (col0 < q_cols + kv_cols) { o.out = a.k; o.out_cols = kv_cols; o.out_col0 = col0 - q_cols; }
-  else { o.out = a.v; o.out_cols = kv_cols; o.out_col0 = col0 - q_cols - kv_cols; o.rotate = false; }
+  else if (col0 < q_cols + kv_cols) { o.out = a.k; o.fused = a.k_fused; o.out_cols = kv_cols; o.out_col0 = col0 - q_cols; }
+  else { o.out = a.v; o.fused = a.v_fused; o.out_cols = kv_cols; o.out_col0 = col0 - q_cols - kv_cols; o.rotate = false; }
   return o;
 }
 
@@ -345,6 +353,7 @@ __device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, co
   column_task<STYLE>(a, tk, e0, e1, i0);
   bool zero[NT];
   int32_t posv[NT];
+  int64_t fdst[NT];                                    // row of the fused cache (-1: none)
   u32x4 w4[NT][2];                                     // the row's 16 residual values
   float2 rho[8];                                       // frequencies of this thread's 8 pairs, in turns per position
   if (ot.rotate) {
@@ -356,7 +365,12 @@ __device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, co
     const int64_t m = m0 + r0 + t * RSTEP;
     zero[t] = false;
     posv[t] = 0;
+    fdst[t] = -1;
     if (m < a.M) {
+      if (ot.fused) {
+        const int64_t d = a.dst_rows[m];
+        if (d >= 0 && d < a.fused_rows) fdst[t] = d;
+      }
       if (a.gather) {                                  // an index outside x produces a zero row
         const int64_t idx = a.gather[m];
         zero[t] = idx < 0 || idx >= a.x_rows;
@@ -407,9 +421,15 @@ __device__ __forceinline__ void store_tile(const QkvArgs& a, const float* sC, co
 #pragma unroll
       for (int p = 0; p < 16; ++p) o[p] = f[p];
     }
+    const u32x4 lo16 = Vec16<bf16_t>::pack(o), hi16 = Vec16<bf16_t>::pack(o + 8);
     bf16_t* dst = ot.out + m * ot.out_cols + ot.out_col0;
-    *reinterpret_cast<u32x4*>(dst + e0) = Vec16<bf16_t>::pack(o);
-    *reinterpret_cast<u32x4*>(dst + e1) = Vec16<bf16_t>::pack(o + 8);
+    *reinterpret_cast<u32x4*>(dst + e0) = lo16;
+    *reinterpret_cast<u32x4*>(dst + e1) = hi16;
+    if (fdst[t] >= 0) {
+      bf16_t* fd = ot.fused + fdst[t] * ot.out_cols + ot.out_col0;
+      *reinterpret_cast<u32x4*>(fd + e0) = lo16;
+      *reinterpret_cast<u32x4*>(fd + e1) = hi16;
+    }
   }
 }
 
@@ -783,7 +803,8 @@ size_t qkv_workspace(const qcf_layer_desc& L, int64_t M) {
 }
 
 qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, const int32_t* gather,
-                      int64_t M, const void* w, const int32_t* pos, void* q, void* k, void* v, void* ws,
+                      int64_t M, const void* w, const int32_t* pos, void* q, void* k, void* v,
+                      const int32_t* dst_rows, void* k_fused, void* v_fused, int64_t fused_rows, void* ws,
                       hipStream_t st) {
   const int H = L.n_q_heads, Hkv = L.n_kv_heads, D = L.head_dim;
   const int Ntot = (H + 2 * Hkv) * D;
@@ -800,6 +821,8 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
     a.m_tiles = 0; a.n_tiles = 0;
     a.q = static_cast<bf16_t*>(q); a.k = static_cast<bf16_t*>(k); a.v = static_cast<bf16_t*>(v);
     a.plain = 0; a.residual = nullptr;
+    a.dst_rows = dst_rows; a.k_fused = static_cast<bf16_t*>(k_fused); a.v_fused = static_cast<bf16_t*>(v_fused);
+    a.fused_rows = fused_rows;
     const bool big = prefer_256_rows(M, Ntot / kBN, L.d_model);
     // (the specialised kernels address x with 32-bit byte offsets)
     const bool ws_ok = (uint64_t)x_rows * (uint64_t)L.d_model * 2u < (1ull << 32);
@@ -832,7 +855,9 @@ qcf_status launch_qkv(const qcf_layer_desc& L, const void* x, int64_t x_rows, co
         y, M, cs, H, Hkv, D, L.rope_style, static_cast<float*>(q), static_cast<float*>(k),
         static_cast<float*>(v));
   }
-  return check_launch("qkv rope");
+  QCF_TRY_LAUNCH("qkv rope");
+  if (dst_rows) return launch_scatter(L, k, v, dst_rows, M, k_fused, v_fused, fused_rows, st);   // (k, v given: checked by the caller)
+  return QCF_OK;
 }
 
 // ---- plain linear map, RMSNorm, gated SiLU (rest of the layer for the recomputed rows) -----------------
@@ -865,6 +890,7 @@ qcf_status launch_linear(const qcf_layer_desc& L, const void* x, int64_t M, int3
     a.q = static_cast<bf16_t*>(out); a.k = nullptr; a.v = nullptr;
     a.plain = 1;
     a.residual = static_cast<const bf16_t*>(residual);
+    a.dst_rows = nullptr; a.k_fused = nullptr; a.v_fused = nullptr; a.fused_rows = 0;
     const bool big = prefer_256_rows(M, N / kBN, K);
     const bool ws_ok = (uint64_t)M * (uint64_t)K * 2u < (1ull << 32);
     if (big && ws_ok) return run_ws<2>(LL, a, st);

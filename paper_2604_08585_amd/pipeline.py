@@ -130,6 +130,12 @@ def step_qkv(L: DeviceLayer) -> None:
                          L.q_sel, L.k_sel, L.v_sel, L.ws_qkv)
 
 
+def step_qkv_scatter(L: DeviceLayer) -> None:
+    """Projection and write-back in one call (same results as step_qkv followed by step_scatter)."""
+    qb.qcf_recompute_qkv_scatter(L.desc, L.x_ctx, L.total_ctx, L.sel_row, L.total_sel, L.w_qkv, L.sel_pos,
+                                 L.q_sel, L.k_sel, L.v_sel, L.sel_row, L.k_fused, L.v_fused, L.total_ctx, L.ws_qkv)
+
+
 def step_scatter(L: DeviceLayer) -> None:
     qb.qcf_scatter(L.desc, L.k_sel, L.v_sel, L.sel_row, L.total_sel, L.k_fused, L.v_fused, L.total_ctx)
 
@@ -160,9 +166,15 @@ STEPS = (("rerope", step_rerope), ("score", step_score), ("select", step_select)
          ("qkv", step_qkv), ("scatter", step_scatter), ("attn", step_attn))
 
 
-def enqueue_layer(L: DeviceLayer, critical: bool = True) -> None:
-    """rerope -> [score -> select at the critical layer] -> qkv -> scatter -> attn."""
-    for name, fn in STEPS:
+# the same path with the projection and the write-back in one call
+FUSED_STEPS = (("rerope", step_rerope), ("score", step_score), ("select", step_select),
+               ("qkv_scatter", step_qkv_scatter), ("attn", step_attn))
+
+
+def enqueue_layer(L: DeviceLayer, critical: bool = True, fused: bool = True) -> None:
+    """rerope -> [score -> select at the critical layer] -> qkv -> scatter -> attn; with `fused` the projection
+    writes the cache rows itself (qcf_recompute_qkv_scatter), otherwise qcf_scatter runs as a call of its own."""
+    for name, fn in (FUSED_STEPS if fused else STEPS):
         if not critical and name in ("score", "select"):
             continue
         fn(L)

@@ -21,7 +21,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = qb.load_library()
     names = declared_symbols()
-    assert len(names) == 23 and set(names) == set(qb.EXPORTS)
+    assert len(names) == 24 and set(names) == set(qb.EXPORTS)
     for n in names:
         assert hasattr(lib, n), n
     assert lib.qcf_version() >= 100
@@ -80,6 +80,16 @@ def test_bad_arguments_are_rejected_on_the_host():
     # a gather table over an empty x (an index outside x falls back to row 0, which must exist)
     assert lib.qcf_recompute_qkv(C.byref(d), fake, 0, fake, 4, fake, fake, fake, fake, fake, fake, 1 << 20, None) == 1
     assert b"no rows" in lib.qcf_last_error()
+    # the one-call form of projection + write-back needs the K/V outputs and the cache
+    assert lib.qcf_recompute_qkv_scatter(C.byref(d), fake, 8, fake, 4, fake, fake, fake, None, fake, fake, fake, fake, 8,
+                                         fake, 1 << 20, None) == 1
+    assert b"k_out" in lib.qcf_last_error()
+    assert lib.qcf_recompute_qkv_scatter(C.byref(d), fake, 8, fake, 4, fake, fake, fake, fake, fake, None, fake, fake, 8,
+                                         fake, 1 << 20, None) == 1
+    assert lib.qcf_recompute_qkv_scatter(C.byref(d), fake, 8, fake, 4, fake, fake, fake, fake, fake, fake, fake, None, 8,
+                                         fake, 1 << 20, None) == 1
+    assert lib.qcf_recompute_qkv_scatter(C.byref(d), None, 0, None, 0, None, None, None, None, None, None, None, None, 0,
+                                         None, 0, None) == 0
     # rest-of-the-layer calls: sizes must be multiples of 8, the f32 / odd-shape path needs its workspace
     assert lib.qcf_linear(C.byref(d), fake, 4, 20, fake, 64, None, fake, None, 0, None) == 1
     assert lib.qcf_linear(C.byref(d), fake, 4, 64, fake, 128, None, None, None, 0, None) == 1

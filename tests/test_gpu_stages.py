@@ -398,6 +398,49 @@ def test_scatter(dtype):
     assert np.array_equal(to_np(dk), rk) and np.array_equal(to_np(dv), rv)
 
 
+@pytest.mark.parametrize("sh,M", [(shape_f32(), 60), (shape_bf16(), 77), (shape_bf16(style=1), 300),
+                                  (shape_bf16(d_model=256, H=32, Hkv=8), 256 * 4 + 19)],
+                         ids=["f32-generic", "bf16-128-row-tiles", "bf16-il", "bf16-256-row-tiles"])
+def test_qkv_scatter_in_one_call(sh, M):
+    # projection and write-back in one call: outputs and cache equal those of the two separate calls bit for bit,
+    # the cache rows equal the oracle's scatter of the oracle's K/V; destination rows outside the cache are skipped
+    say(f"qkv+scatter {sh} M={M}")
+    rng = np.random.default_rng(31)
+    dt = inputs.torch_dtype(sh.dtype)
+    H, Hkv, D = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    T = M + 200
+    x = rnd(rng, (T, sh.d_model), sh.dtype)
+    w = rnd(rng, (sh.qkv_rows, sh.d_model), sh.dtype, std=1 / math.sqrt(sh.d_model))
+    rows = np.sort(rng.choice(T, size=M, replace=False)).astype(np.int32)
+    pos = rows.copy()
+    dst = rows.copy()
+    dst[3] = -1                   # skipped
+    dst[M - 2] = T + 5            # skipped
+    kf, vf = rnd(rng, (T, Hkv, D), sh.dtype), rnd(rng, (T, Hkv, D), sh.dtype)
+    desc = qb.make_desc(sh)
+    dx, dw = to_dev(x, dt), to_dev(w, dt)
+    # two calls
+    q1 = torch.empty((M, H, D), dtype=dt, device=DEV); k1 = torch.empty((M, Hkv, D), dtype=dt, device=DEV); v1 = torch.empty_like(k1)
+    kf1, vf1 = to_dev(kf, dt), to_dev(vf, dt)
+    qb.qcf_recompute_qkv(desc, dx, T, i32(rows), M, dw, i32(pos), q1, k1, v1)
+    qb.qcf_scatter(desc, k1, v1, i32(dst), M, kf1, vf1, T)
+    # one call
+    q2 = torch.full_like(q1, 7.0); k2 = torch.full_like(k1, 7.0); v2 = torch.full_like(v1, 7.0)
+    kf2, vf2 = to_dev(kf, dt), to_dev(vf, dt)
+    qb.qcf_recompute_qkv_scatter(desc, dx, T, i32(rows), M, dw, i32(pos), q2, k2, v2, i32(dst), kf2, vf2, T)
+    torch.cuda.synchronize()
+    for a, b, name in ((q1, q2, "q"), (k1, k2, "k"), (v1, v2, "v"), (kf1, kf2, "k_fused"), (vf1, vf2, "v_fused")):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), name
+    rq, rk, rv = orc.recompute_qkv(x[rows], w, pos, H, Hkv, D, sh.rope_base, sh.rope_style)
+    ok = (dst >= 0) & (dst < T)
+    ek, ev = orc.scatter(kf, vf, rk[ok], rv[ok], dst[ok])
+    assert_close(to_np(kf2), ek, sh.dtype, "k_fused vs oracle")
+    assert_close(to_np(vf2), ev, sh.dtype, "v_fused vs oracle")
+    untouched = np.setdiff1d(np.arange(T), dst[ok])
+    assert np.array_equal(to_np(kf2)[untouched], kf[untouched]) and np.array_equal(to_np(vf2)[untouched], vf[untouched])
+    assert_close(to_np(q2), rq, sh.dtype, "q")
+
+
 # ------------------------------------------------------------------ attn
 
 def _attn_case(sh, T_list, N_list, seed, pos0=None, probe_rows=0, q_std=1.0):
