@@ -321,6 +321,7 @@ def test_qkv_large_tile_config_and_partial_outputs():
     # enough row tiles that the 256-row tile configuration is chosen (200 tiles of 256 x 128)
     sh = shape_bf16(d_model=256, H=32, Hkv=8, D=128)
     _qkv_case(sh, 256 * 4 + 19, 1300, seed=21)
+    _qkv_case(sh, 256 * 17 + 5, 5000, seed=24)     # 18 row tiles: the workgroup order that deals row tiles to the XCDs
     _qkv_case(shape_bf16(), 40, 40, seed=22, gather=False, outputs=(True, False, False))   # probe rows: Q only
     _qkv_case(shape_bf16(), 70, 100, seed=23, outputs=(False, True, True))
 
