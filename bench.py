@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the per-layer KV-cache fusion hot path on one MI355X.
 
-A step is one pass of all six calls (rerope, score, select, recompute_qkv, scatter,
+A step is one pass of the whole path (rerope, score, select, recompute_qkv + scatter in one call,
 recompute_attn) over one critical layer of the 8K-context workload (16 ragged chunks, 8192
 context tokens, 80 probe rows, Llama-3-8B-shaped layer, bf16, recompute ratio 15 %).  Inputs
 are resident in HBM before the timed region; several independent copies of the layer's buffers
@@ -228,14 +228,19 @@ def pipeline_leg(L, chunk_lens, n_layers=8, reps=3):
 
 
 def kernel_source_sha():
-    """Fingerprint of the kernel sources; the HBM traffic table records the one it was measured with."""
+    """Fingerprint of the kernel sources (comments and blank lines left out); the HBM traffic table records the one
+    it was measured with."""
     import hashlib
+    import re
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2604_08585_amd", "csrc")
     for name in sorted(os.listdir(csrc)):
         if name.endswith((".hip", ".h")):
+            text = open(os.path.join(csrc, name), encoding="utf-8").read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            lines = [re.sub(r"//.*$", "", ln).rstrip() for ln in text.split("\n")]
             h.update(name.encode())
-            h.update(open(os.path.join(csrc, name), "rb").read())
+            h.update("\n".join(ln for ln in lines if ln.strip()).encode())
     return h.hexdigest()[:16]
 
 
@@ -332,7 +337,7 @@ def main():
     dominant = max([n for n, _ in pipeline.FUSED_STEPS], key=lambda n: per_call[n])
 
     # timed region: exactly `steps` layers back to back, events around the dominant call only (an event
-    # pair around each of the six calls costs several microseconds per layer at this scale)
+    # pair around every call costs several microseconds per layer at this scale)
     wall, dom = run_with_events(args.steps, 0, only=dominant)
     ms_per_step = wall * 1e3 / args.steps
     per_call[dominant] = dom[dominant]
@@ -395,8 +400,8 @@ def main():
     warm_ms = (time.perf_counter() - t0) * 1e3 / warm_steps
 
     # labelled extra: each buffer set's layer captured once into a HIP graph, the graphs replayed in the same
-    # rotation as the timed region (same kernels and buffers; the six launches per layer come from one graph
-    # launch instead of six calls); never the headline value
+    # rotation as the timed region (same kernels and buffers; a layer's launches come from one graph
+    # launch instead of five calls); never the headline value
     graph_ms = None
     if not args.no_graph:
         graphs = []

@@ -1,4 +1,4 @@
-"""ctypes binding of libqcf.so: the same six calls as include/qcf.h, taking torch CUDA
+"""ctypes binding of libqcf.so: the same calls as include/qcf.h, taking torch CUDA
 tensors.  Argument marshalling only - every step runs in the library's HIP kernels.  There is
 no fallback: a missing library raises."""
 from __future__ import annotations

@@ -12,6 +12,8 @@
 // The generic path (f32, or shapes the MFMA tiling does not cover) writes the raw product to
 // the workspace and rotates it in a second kernel with a (cos, sin) table built from float64
 // angles by a small table kernel.
+// qcf_recompute_qkv_scatter: the epilogue of the MFMA path also stores the K and V rows to their rows of the
+// fused cache (step 5 of the path, otherwise a kernel of its own).
 #include <type_traits>
 #include <utility>
 

@@ -1,4 +1,4 @@
-"""One fused layer = the six library calls in order, on buffers allocated once.
+"""One fused layer = the library calls of the path in order, on buffers allocated once.
 
 Marshalling only: this module allocates device buffers through torch, builds the small
 offset tables, and enqueues the calls of binding.py on the current stream.
