@@ -141,6 +141,22 @@ def test_single_token_chunks_and_tiny_context():
     check_layer(wl, 1.0)
 
 
+def test_five_call_layer_equals_six_call_layer():
+    """The layer with projection and write-back in one call (the default) gives the same bits as the layer with
+    qcf_recompute_qkv and qcf_scatter as separate calls."""
+    wl = inputs.make_config(2, orc.PlantOps(), scale=1 / 8)
+    L = pipeline.upload(wl, DEV)
+    pipeline.enqueue_layer(L, fused=False)
+    torch.cuda.synchronize()
+    n = L.total_sel
+    six = dict(k_fused=L.k_fused[:L.total_ctx].clone(), v_fused=L.v_fused[:L.total_ctx].clone(), q_sel=L.q_sel[:n].clone(),
+               k_sel=L.k_sel[:n].clone(), v_sel=L.v_sel[:n].clone(), o_sel=L.o_sel[:n].clone(), lse=L.lse[:n].clone())
+    five = pipeline.fuse_layer(L)
+    torch.cuda.synchronize()
+    for key, t in six.items():
+        assert torch.equal(t.view(torch.uint8), five[key].view(torch.uint8)), key
+
+
 def test_repeat_layer_is_bit_stable():
     wl = inputs.make_config(2, orc.PlantOps(), scale=1 / 8)
     L = pipeline.upload(wl, DEV)
