@@ -13,6 +13,10 @@
 //           a log2-sum-exp per row (in a fixed order, so all workgroups get the same value); logits
 //           again, p = exp2(logit - lse), summed over the rows of the group -> per-KV-head column sums;
 //   reduce  fixed-order sum over KV heads, times 1/(R*H).
+// Launches that are resident at once (one workgroup per compute unit at most, up to 320 probe rows per KV
+// group) take a single kernel instead (score_fused, further down): the exponentials of pass 1 stay in registers
+// across a grid-wide exchange of the per-row partials, so the keys are read once and no second pass or reduce
+// kernel runs.
 // No floating-point atomics anywhere, so scores (and the indices selected from them) are
 // bit-stable from run to run.
 //
